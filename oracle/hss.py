@@ -1,0 +1,225 @@
+"""Randomized symmetric HSS compression of a Gaussian kernel matrix (oracle; test
+infrastructure).
+
+The paper treats HSS compression as a library call (Algorithm 3, first line)
+and cites the literature for it: the HSS form (hierarchical 2x2 partition with
+low-rank off-diagonal blocks, Sec. 3.1), randomized sampling of block rows with
+oversampling, and per-block truncation to a tolerance eps giving a global
+O(eps) error (end of Sec. 3.2).  This file writes that construction out
+sequentially, node by node, from those definitions:
+
+  leaf t (rows I_t):   D_t = K(I_t, I_t)
+                       S_t = S(I_t,:) - D_t Omega(I_t,:)          (= K(I_t, rest) Omega(rest,:))
+                       row interpolative decomposition  S_t ~= U_t S_t(J_t,:)
+  inner t = (a, b):    B_ab = K(skel_a, skel_b)                   (entries of K itself)
+                       S_t = [S~_a - B_ab Om~_b ; S~_b - B_ab^T Om~_a]
+                       row ID again, unless t is the root
+  with  S~_t = S_t(J_t,:),  Om~_t = U_t^T [Om~_a; Om~_b]  (Omega(I_t,:) at leaves).
+
+Represented matrix: diagonal leaf blocks D_t exactly; K~(I_a, I_b) = Uh_a B_ab Uh_b^T
+with Uh_leaf = U_leaf and Uh_t = blkdiag(Uh_a, Uh_b) U_t.
+
+Nodes are numbered in heap order: root 0, children of t are 2t+1 and 2t+2; the
+leaves are the last 2^L nodes, left to right.
+
+Which rows an ID picks (and so the ranks) is not unique: "parity unpinned".
+What is pinned (tests/test_oracle_hss.py): reconstruction error <= tolerance
+against the dense kernel, exactness when the sample is wide and the tolerance
+tiny, the rank-one limit, densify/mat-vec agreement.
+"""
+import numpy as np
+import scipy.linalg as sla
+
+from .kernel import gaussian_kernel
+
+
+def sample(Fp, Omega, h, block=512):
+    """S = K(Fp, Fp) @ Omega with K never held whole (row-blocked)."""
+    n = Fp.shape[0]
+    S = np.empty((n, Omega.shape[1]), dtype=np.float64)
+    for i0 in range(0, n, block):
+        i1 = min(n, i0 + block)
+        S[i0:i1] = gaussian_kernel(Fp[i0:i1], Fp, h) @ Omega
+    return S
+
+
+def row_id(A, rel_tol, abs_tol, kmax):
+    """Row interpolative decomposition  A ~= U A[J, :].
+
+    Householder QR with column pivoting of A^T.  Rank k = number of leading
+    pivots with |R_jj| > max(rel_tol*|R_00|, abs_tol), capped at kmax.
+    Returns (J, U): J (k,) local row indices, U (rows, k) with U[J] = I_k and
+    the remaining rows T = (R11^{-1} R12)^T.
+    """
+    rows = A.shape[0]
+    if rows == 0 or A.shape[1] == 0:
+        return np.zeros(0, dtype=np.int64), np.zeros((rows, 0))
+    R, piv = sla.qr(A.T, mode="r", pivoting=True)
+    d = np.abs(np.diag(R))
+    thr = max(rel_tol * d[0], abs_tol) if d.size else 0.0
+    k = 0
+    while k < d.size and k < kmax and d[k] > thr:
+        k += 1
+    J = np.asarray(piv[:k], dtype=np.int64)
+    U = np.zeros((rows, k), dtype=np.float64)
+    if k:
+        U[J, np.arange(k)] = 1.0
+        if k < rows:
+            T = sla.solve_triangular(R[:k, :k], R[:k, k:], lower=False)   # k x (rows-k)
+            U[piv[k:], :] = T.T
+    return J, U
+
+
+class HSS:
+    """Container for the generators of a symmetric HSS matrix."""
+
+    def __init__(self, n, leaf):
+        self.n = int(n)
+        self.leaf = int(leaf)
+        nl = self.n // self.leaf
+        if nl * self.leaf != self.n or nl & (nl - 1) or nl < 1:
+            raise ValueError("n must be leaf * 2^L")
+        self.L = nl.bit_length() - 1
+        self.nnodes = 2 * nl - 1
+        self.D = [None] * nl                    # leaf diagonal blocks, left to right
+        self.U = [None] * self.nnodes           # (size_t, k_t); None at the root
+        self.J = [None] * self.nnodes           # local skeleton rows
+        self.B = [None] * self.nnodes           # (k_a, k_b) at inner nodes
+        self.skel = [None] * self.nnodes        # global (permuted-order) skeleton indices
+
+    def first_leaf(self):
+        return (1 << self.L) - 1
+
+    def is_leaf(self, t):
+        return t >= self.first_leaf()
+
+    def level_nodes(self, l):
+        return range((1 << l) - 1, (1 << (l + 1)) - 1)
+
+    def rank(self, t):
+        return 0 if self.U[t] is None else self.U[t].shape[1]
+
+    def size(self, t):
+        if self.is_leaf(t):
+            return self.leaf
+        return self.rank(2 * t + 1) + self.rank(2 * t + 2)
+
+    def ranks(self):
+        return np.array([self.rank(t) for t in range(self.nnodes)], dtype=np.int64)
+
+
+def compress(Fp, h, leaf, Omega, rel_tol, abs_tol=0.0, kmax=None, S=None):
+    """Build the HSS generators of K(Fp, Fp) from the random sample S = K Omega.
+
+    Fp: points already in cluster-tree order.  Omega: (n, s).  kmax: rank cap
+    (default s).  S may be passed if already computed.
+    """
+    Fp = np.asarray(Fp, dtype=np.float64)
+    n = Fp.shape[0]
+    s = Omega.shape[1]
+    if kmax is None:
+        kmax = s
+    H = HSS(n, leaf)
+    if S is None:
+        S = sample(Fp, Omega, h)
+    Sred = [None] * H.nnodes     # S~_t
+    Ored = [None] * H.nnodes     # Om~_t
+    fl = H.first_leaf()
+    for l in range(H.L, -1, -1):
+        for t in H.level_nodes(l):
+            if H.is_leaf(t):
+                i = t - fl
+                rows = np.arange(i * leaf, (i + 1) * leaf)
+                Dt = gaussian_kernel(Fp[rows], Fp[rows], h)
+                H.D[i] = Dt
+                St = S[rows] - Dt @ Omega[rows]
+                Ot = Omega[rows]
+                idx = rows
+            else:
+                a, b = 2 * t + 1, 2 * t + 2
+                Bab = gaussian_kernel(Fp[H.skel[a]], Fp[H.skel[b]], h)
+                H.B[t] = Bab
+                St = np.vstack([Sred[a] - Bab @ Ored[b], Sred[b] - Bab.T @ Ored[a]])
+                Ot = np.vstack([Ored[a], Ored[b]])
+                idx = np.concatenate([H.skel[a], H.skel[b]])
+                Sred[a] = Sred[b] = Ored[a] = Ored[b] = None
+            if t == 0:
+                break
+            J, U = row_id(St, rel_tol, abs_tol, kmax)
+            H.J[t], H.U[t] = J, U
+            H.skel[t] = idx[J]
+            Sred[t] = St[J]
+            Ored[t] = U.T @ Ot
+    return H
+
+
+def nested_basis(H, t):
+    """Uh_t: (number of points under t, k_t)."""
+    if H.is_leaf(t):
+        return H.U[t]
+    a, b = 2 * t + 1, 2 * t + 2
+    Ua, Ub = nested_basis(H, a), nested_basis(H, b)
+    blk = np.zeros((Ua.shape[0] + Ub.shape[0], Ua.shape[1] + Ub.shape[1]))
+    blk[:Ua.shape[0], :Ua.shape[1]] = Ua
+    blk[Ua.shape[0]:, Ua.shape[1]:] = Ub
+    return blk @ H.U[t]
+
+
+def densify(H):
+    """The n x n matrix the generators represent (small n only)."""
+    n, m = H.n, H.leaf
+    A = np.zeros((n, n))
+    fl = H.first_leaf()
+    for i in range(n // m):
+        A[i * m:(i + 1) * m, i * m:(i + 1) * m] = H.D[i]
+
+    def span(t):
+        l = (t + 1).bit_length() - 1
+        i = t - ((1 << l) - 1)
+        w = n >> l
+        return i * w, (i + 1) * w
+
+    for t in range(fl):
+        a, b = 2 * t + 1, 2 * t + 2
+        Ua, Ub = nested_basis(H, a), nested_basis(H, b)
+        blk = Ua @ H.B[t] @ Ub.T
+        a0, a1 = span(a)
+        b0, b1 = span(b)
+        A[a0:a1, b0:b1] = blk
+        A[b0:b1, a0:a1] = blk.T
+    return A
+
+
+def matvec(H, x):
+    """y = K~ x for x in cluster-tree order: up-sweep x~ = U^T(.), down-sweep
+    through B, leaves add D x (the standard two-pass HSS product)."""
+    x = np.asarray(x, dtype=np.float64)
+    m = H.leaf
+    fl = H.first_leaf()
+    xt = [None] * H.nnodes
+    for t in range(H.nnodes - 1, 0, -1):
+        if H.is_leaf(t):
+            i = t - fl
+            xt[t] = H.U[t].T @ x[i * m:(i + 1) * m]
+        else:
+            xt[t] = H.U[t].T @ np.concatenate([xt[2 * t + 1], xt[2 * t + 2]])
+    g = [None] * H.nnodes
+    y = np.empty_like(x)
+    for t in range(H.nnodes):
+        if H.is_leaf(t):
+            i = t - fl
+            y[i * m:(i + 1) * m] = H.D[i] @ x[i * m:(i + 1) * m]
+            if t != 0:
+                y[i * m:(i + 1) * m] += H.U[t] @ g[t]
+            continue
+        a, b = 2 * t + 1, 2 * t + 2
+        ka = H.rank(a)
+        if t == 0:
+            ha = np.zeros(ka)
+            hb = np.zeros(H.rank(b))
+        else:
+            hv = H.U[t] @ g[t]
+            ha, hb = hv[:ka], hv[ka:]
+        g[a] = ha + H.B[t] @ xt[b]
+        g[b] = hb + H.B[t].T @ xt[a]
+    return y
