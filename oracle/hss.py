@@ -223,3 +223,30 @@ def matvec(H, x):
         g[a] = ha + H.B[t] @ xt[b]
         g[b] = hb + H.B[t].T @ xt[a]
     return y
+
+
+def psd_shift(H, safety=1.1, tol=1e-3):
+    """delta >= 0 such that K~ + delta*I is (numerically) positive semidefinite.
+
+    The paper's trainer presupposes a convex approximate problem (eq. 8): ADMM is
+    called convergent and the ULV factors are those of a definite matrix.  When
+    the ranks saturate, the compressed matrix can lose definiteness; the guard
+    adds delta = safety * max(0, -lambda_min(K~)) to the diagonal (only the leaf
+    blocks change, exactly as for the beta shift).  delta = 0 whenever K~ is
+    already positive semidefinite.  lambda_min comes from a Lanczos run on the
+    HSS mat-vec (library routine)."""
+    import scipy.sparse.linalg as spla
+    if H.n <= 512:
+        lam = float(np.linalg.eigvalsh(densify(H))[0])
+    else:
+        op = spla.LinearOperator((H.n, H.n), matvec=lambda v: matvec(H, v), dtype=np.float64)
+        lam = float(spla.eigsh(op, k=1, which="SA", tol=tol, return_eigenvectors=False)[0])
+    return safety * max(0.0, -lam)
+
+
+def add_diagonal(H, delta):
+    """K~ <- K~ + delta*I (in place, leaf diagonal blocks only)."""
+    if delta != 0.0:
+        for i in range(len(H.D)):
+            H.D[i] = H.D[i] + delta * np.eye(H.leaf)
+    return H

@@ -174,3 +174,18 @@ def test_planted_mistakes_are_caught():
     H.B[t] = keep
     assert np.linalg.norm(x_bad - ref) > 1e-6 * np.linalg.norm(ref)
     assert np.linalg.norm(y_bad - (A - beta * np.eye(n)) @ b) > 1e-6 * np.linalg.norm(b)
+
+
+def test_psd_shift_restores_definiteness_and_is_zero_when_not_needed():
+    # saturated ranks: the compressed matrix is indefinite, the guard repairs it
+    Fp, Om, H, _ = _compress(1024, 8, 1.5, 64, 64, 1e-5, kmax=54)
+    lam = np.linalg.eigvalsh(hss.densify(H))[0]
+    assert lam < -1.0
+    delta = hss.psd_shift(H)
+    assert -lam <= delta <= 1.2 * -lam
+    hss.add_diagonal(H, delta)
+    assert np.linalg.eigvalsh(hss.densify(H))[0] >= 0.0
+    # accurate compression of a well-conditioned kernel: no shift
+    Fp, Om, H2, _ = _compress(512, 2, 0.05, 32, 128, 1e-8, kmax=118)
+    assert np.linalg.eigvalsh(hss.densify(H2))[0] > 0
+    assert hss.psd_shift(H2) == 0.0
