@@ -1,0 +1,156 @@
+/*
+ * hss_svm.h -- C ABI of the shifted-kernel-solve path of the ADMM + HSS nonlinear-SVM trainer
+ * (Cipolla & Gondzio, "Training very large scale nonlinear SVMs using ADMM coupled with HSS
+ * kernel approximations").
+ *
+ * The library runs on one AMD gfx950 GPU.  It trains
+ *
+ *        min_x  1/2 x^T Y K Y x - e^T x     s.t.  y^T x = 0,  0 <= x <= C            (eq. 1)
+ *
+ * with the Gaussian kernel K_ij = exp(-||f_i - f_j||^2 / (2 h^2)) (Sec. 1.1 / Sec. 3.3), following
+ * Algorithm 3: HSS compression of K, shift by beta*I, ULV factorization, then closed-form ADMM
+ * iterations (Algorithm 2) that each apply (K~ + beta I)^{-1} once.  What is cached follows Sec. 3.2:
+ * the compression depends only on (F, h), the factorization on (F, h, beta), an ADMM run on
+ * (F, h, beta, C).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses valid on the GPU that was current at hss_create;
+ *     "host" pointers are ordinary host memory.  All floating point data is IEEE double.
+ *   - F is point-major: the r features of point i are F[i*r .. i*r+r-1] (the paper's r x d matrix
+ *     F_train stored column by column).  y holds exactly -1.0 or +1.0.
+ *   - Every vector that crosses this boundary (rhs, x, z, mu, y, decision values) is in the
+ *     caller's original point order.  The cluster-tree permutation is internal.
+ *   - The caller owns every buffer it passes.  The library copies what it needs during the call,
+ *     except F, which hss_compress copies into its own permuted storage as well: nothing of the
+ *     caller's is retained after a call returns.
+ *   - Work is enqueued on the HIP stream given to hss_create (borrowed, never destroyed).  Calls
+ *     that return host scalars or need ranks on the host synchronise that stream; all others are
+ *     asynchronous with respect to the host.
+ *   - Return value: 0 = ok; < 0 = error, nothing useful was written; > 0 = bitwise OR of HSS_W*
+ *     warnings, results were written.  No call aborts, throws, or prints.
+ *   - A context is not thread-safe.  Calls on one context must not overlap.
+ */
+#ifndef HSS_SVM_H
+#define HSS_SVM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hss_ctx hss_ctx;
+
+/* errors */
+#define HSS_OK            0
+#define HSS_EINVAL       (-1)  /* bad argument: n, r, leaf, tol, h, beta, C out of range; n != leaf*2^L; null pointer */
+#define HSS_ESTATE       (-2)  /* call out of order: solve before factor, factor before compress, ...            */
+#define HSS_ENOMEM       (-3)  /* device or host allocation failed                                                */
+#define HSS_EHIP         (-4)  /* a HIP runtime call failed                                                       */
+#define HSS_EUNSUPPORTED (-5)  /* size outside what the kernels are built for (see hss_compress)                 */
+/* warnings (bit mask) */
+#define HSS_WRANK      1   /* some node hit the rank cap: the requested tolerance is not guaranteed               */
+#define HSS_WPIVOT     2   /* a tiny pivot was met while factoring: K~ + beta I is close to singular               */
+#define HSS_WNOMARGIN  4   /* the margin set {j : 0 < z_j < C} is empty: bias returned as 0                        */
+#define HSS_WSHIFT     8   /* the definiteness guard added delta > 0 to the diagonal of K~ (see hss_compress)      */
+
+const char* hss_strerror(int code);
+
+/* Create / destroy a context.  hip_stream: a hipStream_t (0 = the null stream); borrowed. */
+int  hss_create(hss_ctx** out, void* hip_stream);
+void hss_destroy(hss_ctx* ctx);
+
+/* Options; set before hss_compress.
+ *   i64: "sample_width" s   number of random columns (default 128; padded with zero columns to a multiple of 128 inside)
+ *        "oversample"   p   rank cap is s - p unless "max_rank" is set (default 10)   (oversampling, end of Sec. 3.2)
+ *        "max_rank"         explicit rank cap per node (default 0 = s - p)
+ *        "seed"             seed of the counter-based generator that draws Omega (default 0)
+ *        "psd_guard"        1 (default): after compression estimate lambda_min(K~) and, if negative,
+ *                           add delta = 1.1*|lambda_min| to the diagonal so that the approximate
+ *                           problem (eq. 8) stays convex, as Algorithm 3 presupposes; 0: off
+ *   f64: "abs_tol"          absolute pivot threshold of the interpolative decompositions (default 1e-8) */
+int hss_set_i64(hss_ctx* ctx, const char* key, int64_t v);
+int hss_set_f64(hss_ctx* ctx, const char* key, double v);
+
+/* S = K(F,F) * Omega without forming K (the randomized range sampling the compression is built on,
+ * end of Sec. 3.2).  F (dev, n x r), Omega (dev, n x s row-major), S_out (dev, n x s row-major), rows in
+ * the order of F.  Stand-alone: needs no prior call and leaves the context's compressed matrix alone.
+ * 1 <= r <= 96, s >= 1. */
+int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h,
+                      const double* Omega_dev, int32_t s, double* S_out_dev);
+
+/* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection on the
+ * coordinate of largest variance), random sampling S = K Omega, interpolative decompositions level by
+ * level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,
+ * 1 <= r <= 96, h > 0, 0 < tol < 1.  Pivots of each decomposition are kept while
+ * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 (EUNSUPPORTED beyond).
+ * Drops any previous compression and factorization held by the context.
+ * hss_compress draws Omega itself (Philox4x32-10 + Box-Muller, option "seed");
+ * hss_compress_with_samples takes Omega (dev, n x s row-major, rows in the order of F) from the caller. */
+int hss_compress(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r,
+                 double h, int32_t leaf, double tol);
+int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r,
+                              double h, int32_t leaf, double tol, const double* Omega_dev, int32_t s);
+
+/* ULV factorization of K~ + beta I (Algorithm 3, lines 2-3).  beta > 0.  May be called again with another
+ * beta without recompressing; replaces the previous factors. */
+int hss_ulv_factor(hss_ctx* ctx, double beta);
+
+/* rhs <- (K~ + beta I)^{-1} rhs, in place.  rhs (dev, n x nrhs, column-major: each right-hand side is
+ * a contiguous n-vector).  nrhs >= 1. */
+int hss_ulv_solve(hss_ctx* ctx, double* rhs_inout_dev, int32_t nrhs);
+
+/* y_out <- K~ x (with the guard's diagonal shift included).  x, y_out (dev, n); may not alias. */
+int hss_matvec(hss_ctx* ctx, const double* x_dev, double* y_out_dev);
+
+/* ADMM (Algorithm 2 with the precomputation of Algorithm 3), maxit iterations from x = z = mu = 0, then
+ * the averaged bias of eq. (7) with the sign that satisfies the margin condition
+ * (b = mean over M of y_j - (K~ Y z)_j).  If beta differs from the factored beta the library
+ * re-factors first.  x_out, z_out, mu_out (dev, n each; any may be null).  bias_out, n_margin_out
+ * (host; may be null).  The model is z (Algorithm 3 uses z for the bias and the labels). */
+int admm_svm_train(hss_ctx* ctx, double C, double beta, int32_t maxit,
+                   double* x_out_dev, double* z_out_dev, double* mu_out_dev,
+                   double* bias_out_host, int64_t* n_margin_out_host);
+
+/* dec_j = sum_i y_i z_i K(f_i, g_j) + bias with the exact kernel (label loop of Algorithm 3).
+ * G (dev, n_test x r), z (dev, n), dec_out (dev, n_test). */
+int svm_decision(hss_ctx* ctx, const double* G_dev, int64_t n_test, const double* z_dev, double bias,
+                 double* dec_out_dev);
+
+typedef struct hss_stats_t {
+    int64_t n, r, leaf, levels;        /* levels = L (leaves are level L, root level 0)                    */
+    int64_t sample_width, rank_cap;
+    int64_t rank_max, rank_sum;        /* over all non-root nodes                                           */
+    int64_t nodes_at_cap;              /* nodes whose rank hit the cap                                      */
+    int64_t generator_bytes;           /* D, U, B as stored                                                 */
+    int64_t factor_bytes;              /* bytes of the dense operators one solve reads (up-sweep, root, down-sweep) */
+    int64_t factor_bytes_compact;      /* the same sweeps with the factors counted in compact form: per node
+                                          m k (reflectors) + (m-k)^2 (LU of D_ee) + k (m-k) (D_re), read twice     */
+    double  sample_flops;              /* 2 n^2 (s + r) of the last sampling                                */
+    double  delta;                     /* diagonal shift added by the definiteness guard                    */
+    double  beta;                      /* factored beta, or -1                                              */
+    double  t_tree, t_sample, t_levels, t_guard, t_factor;   /* seconds, last call of each phase            */
+    int32_t warnings;                  /* OR of HSS_W* seen since the last compress                         */
+    int32_t reserved;
+} hss_stats_t;
+int hss_stats(hss_ctx* ctx, hss_stats_t* out_host);
+
+/* Export of the generators to host memory (the seam the parity tests use to run the oracle on the
+ * same compressed matrix).  Nodes are in heap order: root 0, children of t are 2t+1, 2t+2, leaves last.
+ *   perm   int64[n]           perm[i] = original index of the i-th point in cluster-tree order
+ *   sizes  int32[nnodes]      node size m_t (leaf size at leaves, k_a + k_b above)
+ *   ranks  int32[nnodes]      k_t (0 at the root)
+ *   D      double[nleaf*leaf*leaf]  leaf diagonal blocks, row-major, WITHOUT the guard's shift
+ *   U      double[sum m_t k_t]      row-major (m_t x k_t) per non-root node, heap order
+ *   J      int32[sum k_t]           skeleton rows of each node (local row indices), heap order
+ *   B      double[sum k_a k_b]      row-major (k_a x k_b) per inner node t with children a, b, heap order
+ * hss_export_sizes fills nnodes, u_len, j_len, b_len (host int64 each); hss_export fills the arrays
+ * (host) and *delta_out (host): the represented matrix is the HSS matrix of (D, U, B) plus delta I. */
+int hss_export_sizes(hss_ctx* ctx, int64_t* nnodes, int64_t* u_len, int64_t* j_len, int64_t* b_len);
+int hss_export(hss_ctx* ctx, int64_t* perm, int32_t* sizes, int32_t* ranks, double* D, double* U,
+               int32_t* J, double* B, double* delta_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HSS_SVM_H */

@@ -1,0 +1,260 @@
+// C ABI of libhsssvm (see include/hss_svm.h for the contract of every call).
+#include "ctx.h"
+#include <algorithm>
+#include <cstring>
+
+extern "C" {
+
+const char* hss_strerror(int code) {
+    switch (code) {
+        case HSS_OK: return "ok";
+        case HSS_EINVAL: return "invalid argument";
+        case HSS_ESTATE: return "call out of order";
+        case HSS_ENOMEM: return "out of memory";
+        case HSS_EHIP: return "HIP runtime error";
+        case HSS_EUNSUPPORTED: return "size not supported by the kernels";
+        default: break;
+    }
+    if (code > 0) return "completed with numerical warnings (bit mask of HSS_W*)";
+    return "unknown error";
+}
+
+int hss_create(hss_ctx** out, void* hip_stream) {
+    if (!out) return HSS_EINVAL;
+    hss_ctx* c = new (std::nothrow) hss_ctx();
+    if (!c) return HSS_ENOMEM;
+    c->stream = (hipStream_t)hip_stream;
+    *out = c;
+    return HSS_OK;
+}
+
+void hss_destroy(hss_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    delete ctx;
+}
+
+int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
+    if (!c || !key) return HSS_EINVAL;
+    if (!strcmp(key, "sample_width")) { if (v < 1) return HSS_EINVAL; c->opt_s = v; }
+    else if (!strcmp(key, "oversample")) { if (v < 0) return HSS_EINVAL; c->opt_p = v; }
+    else if (!strcmp(key, "max_rank")) { if (v < 0) return HSS_EINVAL; c->opt_max_rank = v; }
+    else if (!strcmp(key, "seed")) c->opt_seed = v;
+    else if (!strcmp(key, "psd_guard")) c->opt_guard = v ? 1 : 0;
+    else return HSS_EINVAL;
+    return HSS_OK;
+}
+
+int hss_set_f64(hss_ctx* c, const char* key, double v) {
+    if (!c || !key) return HSS_EINVAL;
+    if (!strcmp(key, "abs_tol")) { if (!(v >= 0.0)) return HSS_EINVAL; c->opt_abs_tol = v; }
+    else return HSS_EINVAL;
+    return HSS_OK;
+}
+
+int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h, const double* Omega_dev,
+                      int32_t s, double* S_out_dev) {
+    if (!ctx || !F_dev || !Omega_dev || !S_out_dev || n < 1 || r < 1 || s < 1 || !(h > 0.0)) return HSS_EINVAL;
+    if (r > 96) return HSS_EUNSUPPORTED;
+    hipStream_t st = ctx->stream;
+    const int64_t n_pad = round_up(n, 256);
+    const int r_pad = (int)round_up(r, 4), s_pad = (int)round_up(s, 128);
+    DevBuf Fp, nu, Om, S;
+    HSS_TRY(Fp.reserve(sizeof(double) * n_pad * r_pad));
+    HSS_TRY(nu.reserve(sizeof(double) * n_pad));
+    HSS_TRY(Om.reserve(sizeof(double) * n_pad * s_pad));
+    HSS_TRY(S.reserve(sizeof(double) * n_pad * s_pad));
+    HSS_TRY(gather_pad_rows_launch(st, F_dev, nullptr, Fp.as<double>(), n, n_pad, r, r_pad));
+    HSS_TRY(gather_pad_rows_launch(st, Omega_dev, nullptr, Om.as<double>(), n, n_pad, s, s_pad));
+    HSS_TRY(row_norms_launch(st, Fp.as<double>(), nu.as<double>(), n_pad, r_pad));
+    HSS_TRY(sample_launch(st, Fp.as<double>(), nu.as<double>(), Om.as<double>(), S.as<double>(), n_pad, r_pad, s_pad, h));
+    HIP_TRY(hipMemcpy2DAsync(S_out_dev, sizeof(double) * s, S.p, sizeof(double) * s_pad, sizeof(double) * s, n,
+                             hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));   // the temporaries are freed on return
+    return HSS_OK;
+}
+
+int hss_compress(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,
+                 double tol) {
+    return hss_compress_impl(ctx, F_dev, y_dev, n, r, h, leaf, tol, nullptr, 0);
+}
+
+int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h,
+                              int32_t leaf, double tol, const double* Omega_dev, int32_t s) {
+    if (!Omega_dev) return HSS_EINVAL;
+    return hss_compress_impl(ctx, F_dev, y_dev, n, r, h, leaf, tol, Omega_dev, s);
+}
+
+int hss_ulv_factor(hss_ctx* ctx, double beta) { return ulv_factor_impl(ctx, beta); }
+
+int hss_ulv_solve(hss_ctx* c, double* rhs, int32_t nrhs) {
+    if (!c || !rhs || nrhs < 1) return HSS_EINVAL;
+    if (!c->compressed || !c->factored) return HSS_ESTATE;
+    hipStream_t st = c->stream;
+    Level& ll = c->lev[c->L];
+    const int64_t* perm = c->perm.as<int64_t>();
+    for (int j = 0; j < nrhs; ++j) {
+        double* col = rhs + (size_t)j * c->n;
+        HSS_TRY(vec_gather(st, ll.bvec.as<double>(), col, perm, c->n));
+        HSS_TRY(ulv_solve_perm(c, ll.bvec.as<double>(), ll.xvec.as<double>()));
+        HSS_TRY(vec_scatter(st, col, ll.xvec.as<double>(), perm, c->n));
+    }
+    return HSS_OK;
+}
+
+int hss_matvec(hss_ctx* c, const double* x, double* y) {
+    if (!c || !x || !y) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    hipStream_t st = c->stream;
+    const int64_t* perm = c->perm.as<int64_t>();
+    HSS_TRY(vec_gather(st, c->mv_x.as<double>(), x, perm, c->n));
+    HSS_TRY(hss_matvec_perm(c));
+    HSS_TRY(vec_scatter(st, y, c->mv_y.as<double>(), perm, c->n));
+    return HSS_OK;
+}
+
+int admm_svm_train(hss_ctx* c, double C, double beta, int32_t maxit, double* x_out, double* z_out, double* mu_out,
+                   double* bias_out, int64_t* n_margin_out) {
+    if (!c || !(C > 0.0) || !(beta > 0.0) || maxit < 0) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    int warn = 0;
+    if (!c->factored || c->beta != beta) {
+        int rc = ulv_factor_impl(c, beta);
+        if (rc < 0) return rc;
+        warn |= rc;
+    }
+    hipStream_t st = c->stream;
+    const int64_t n = c->n;
+    const size_t nb = sizeof(double) * n;
+    HSS_TRY(c->v_x.reserve(nb));
+    HSS_TRY(c->v_z.reserve(nb));
+    HSS_TRY(c->v_mu.reserve(nb));
+    HSS_TRY(c->v_w.reserve(nb));
+    HSS_TRY(c->v_e.reserve(nb));
+    Level& ll = c->lev[c->L];
+    double* rhs = ll.bvec.as<double>();
+    double* sol = ll.xvec.as<double>();
+    double* part = c->partial.as<double>();
+    double* scal = c->scal.as<double>();
+    double* w1 = scal + 4;
+    // w = Y K_beta^{-1} e,  w1 = e^T K_beta^{-1} e   (Algorithm 3, lines 4-6)
+    HSS_TRY(fill_launch(st, rhs, n, 1.0));
+    HSS_TRY(ulv_solve_perm(c, rhs, sol));
+    HSS_TRY(vec_dot(st, sol, nullptr, n, part, w1));
+    HSS_TRY(vec_mul(st, c->v_w.as<double>(), c->yp.as<double>(), sol, n));
+    AdmmVecs v{c->v_x.as<double>(), c->v_z.as<double>(), c->v_mu.as<double>(), rhs, sol, c->yp.as<double>(),
+               c->v_w.as<double>()};
+    double* pa = part + VEC_BLOCKS;
+    double* pb = part + 2 * VEC_BLOCKS;
+    HSS_TRY(admm_start(st, v, n, pa));
+    for (int it = 0; it < maxit; ++it) {
+        HSS_TRY(ulv_solve_perm(c, rhs, sol));
+        HSS_TRY(admm_step(st, v, n, C, beta, w1, pa, pb));
+        std::swap(pa, pb);
+    }
+    // bias over the margin set with one HSS mat-vec (eq. 7; sign from the margin condition)
+    double* ebar = c->v_e.as<double>();
+    HSS_TRY(margin_indicator(st, v.z, C, ebar, n));
+    HIP_TRY(hipMemcpyAsync(c->mv_x.p, ebar, nb, hipMemcpyDeviceToDevice, st));
+    HSS_TRY(hss_matvec_perm(c));
+    HSS_TRY(bias_sums(st, v.z, c->yp.as<double>(), c->mv_y.as<double>(), ebar, n, part, scal));
+    double sums[3];
+    HIP_TRY(hipMemcpyAsync(sums, scal, sizeof(sums), hipMemcpyDeviceToHost, st));
+    const int64_t* perm = c->perm.as<int64_t>();
+    if (x_out) HSS_TRY(vec_scatter(st, x_out, v.x, perm, n));
+    if (z_out) HSS_TRY(vec_scatter(st, z_out, v.z, perm, n));
+    if (mu_out) HSS_TRY(vec_scatter(st, mu_out, v.mu, perm, n));
+    HIP_TRY(hipStreamSynchronize(st));
+    const int64_t cnt = (int64_t)(sums[2] + 0.5);
+    double b = 0.0;
+    if (cnt > 0) b = (sums[0] - sums[1]) / (double)cnt;
+    else warn |= HSS_WNOMARGIN;
+    if (bias_out) *bias_out = b;
+    if (n_margin_out) *n_margin_out = cnt;
+    c->warnings |= warn;
+    return warn;
+}
+
+int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, double bias, double* dec) {
+    if (!c || !G || !z || !dec || n_test < 0) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    hipStream_t st = c->stream;
+    HSS_TRY(c->v_u.reserve(sizeof(double) * c->n));
+    HSS_TRY(c->v_e.reserve(sizeof(double) * c->n));
+    // zy in cluster-tree order
+    HSS_TRY(vec_gather(st, c->v_e.as<double>(), z, c->perm.as<int64_t>(), c->n));
+    HSS_TRY(vec_mul(st, c->v_u.as<double>(), c->v_e.as<double>(), c->yp.as<double>(), c->n));
+    HSS_TRY(decision_launch(st, c->Fp.as<double>(), c->v_u.as<double>(), c->n, G, n_test, c->r, c->r_pad, c->h, bias, dec));
+    return HSS_OK;
+}
+
+int hss_stats(hss_ctx* c, hss_stats_t* o) {
+    if (!c || !o) return HSS_EINVAL;
+    memset(o, 0, sizeof(*o));
+    o->n = c->n; o->r = c->r; o->leaf = c->leaf; o->levels = c->L;
+    o->sample_width = c->s; o->rank_cap = c->kcap;
+    if (c->compressed) {
+        for (int l = 1; l <= c->L; ++l)
+            for (int t = 0; t < c->lev[l].N; ++t) {
+                const int k = c->lev[l].rk[t];
+                o->rank_max = std::max<int64_t>(o->rank_max, k);
+                o->rank_sum += k;
+                if (k == c->kcap && k < c->lev[l].msz[t]) o->nodes_at_cap++;
+            }
+    }
+    o->generator_bytes = c->generator_bytes;
+    o->factor_bytes = c->factored ? c->factor_bytes : 0;
+    o->factor_bytes_compact = c->factored ? c->factor_bytes_compact : 0;
+    o->sample_flops = c->sample_flops;
+    o->delta = c->delta;
+    o->beta = c->factored ? c->beta : -1.0;
+    o->t_tree = c->t_tree; o->t_sample = c->t_sample; o->t_levels = c->t_levels; o->t_guard = c->t_guard;
+    o->t_factor = c->t_factor;
+    o->warnings = c->warnings;
+    return HSS_OK;
+}
+
+int hss_export_sizes(hss_ctx* c, int64_t* nnodes, int64_t* u_len, int64_t* j_len, int64_t* b_len) {
+    if (!c || !nnodes || !u_len || !j_len || !b_len) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    *nnodes = (int64_t(2) << c->L) - 1;
+    *u_len = *j_len = *b_len = 0;
+    for (int l = 0; l <= c->L; ++l) {
+        Level& lv = c->lev[l];
+        if (l >= 1) { *u_len += lv.uoff[lv.N]; *j_len += lv.koff[lv.N]; }
+        if (l < c->L) *b_len += lv.boff[lv.N];
+    }
+    return HSS_OK;
+}
+
+int hss_export(hss_ctx* c, int64_t* perm, int32_t* sizes, int32_t* ranks, double* D, double* U, int32_t* J, double* B,
+               double* delta_out) {
+    if (!c || !perm || !sizes || !ranks || !D || !U || !J || !B || !delta_out) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    hipStream_t st = c->stream;
+    memcpy(perm, c->perm_host.data(), sizeof(int64_t) * c->n);
+    HIP_TRY(hipMemcpyAsync(D, c->Dleaf.p, sizeof(double) * (size_t)c->n * c->leaf, hipMemcpyDeviceToHost, st));
+    int64_t node = 0, uo = 0, jo = 0, bo = 0;
+    for (int l = 0; l <= c->L; ++l) {      // heap order = level by level, left to right
+        Level& lv = c->lev[l];
+        for (int t = 0; t < lv.N; ++t, ++node) {
+            sizes[node] = lv.msz[t];
+            ranks[node] = lv.rk[t];
+        }
+        if (l >= 1 && lv.uoff[lv.N] > 0) {
+            HIP_TRY(hipMemcpyAsync(U + uo, lv.U.p, sizeof(double) * lv.uoff[lv.N], hipMemcpyDeviceToHost, st));
+            HIP_TRY(hipMemcpyAsync(J + jo, lv.J.p, sizeof(int32_t) * lv.koff[lv.N], hipMemcpyDeviceToHost, st));
+            uo += lv.uoff[lv.N];
+            jo += lv.koff[lv.N];
+        }
+        if (l < c->L && lv.boff[lv.N] > 0) {
+            HIP_TRY(hipMemcpyAsync(B + bo, lv.B.p, sizeof(double) * lv.boff[lv.N], hipMemcpyDeviceToHost, st));
+            bo += lv.boff[lv.N];
+        }
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    *delta_out = c->delta;
+    return HSS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,127 @@
+// Internal declarations shared by the translation units of libhsssvm (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <vector>
+
+#include "../../include/hss_svm.h"
+
+#define HIP_TRY(expr)                                         \
+    do {                                                      \
+        hipError_t e__ = (expr);                              \
+        if (e__ != hipSuccess) return HSS_EHIP;               \
+    } while (0)
+
+#define HSS_TRY(expr)                                         \
+    do {                                                      \
+        int rc__ = (expr);                                    \
+        if (rc__ < 0) return rc__;                            \
+    } while (0)
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+// ---------------------------------------------------------------------------------------------
+// Device buffer with ownership.
+struct DevBuf {
+    void*  p = nullptr;
+    size_t bytes = 0;
+    DevBuf() = default;
+    DevBuf(const DevBuf&) = delete;
+    DevBuf& operator=(const DevBuf&) = delete;
+    DevBuf(DevBuf&& o) noexcept : p(o.p), bytes(o.bytes) { o.p = nullptr; o.bytes = 0; }
+    DevBuf& operator=(DevBuf&& o) noexcept {
+        if (this != &o) {
+            release();
+            p = o.p; bytes = o.bytes;
+            o.p = nullptr; o.bytes = 0;
+        }
+        return *this;
+    }
+    ~DevBuf() { release(); }
+    void release() {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+    }
+    // (re)allocate when the current block is too small; contents are not preserved
+    int reserve(size_t nbytes) {
+        if (nbytes <= bytes && p) return HSS_OK;
+        release();
+        if (nbytes == 0) nbytes = 8;
+        if (hipMalloc(&p, nbytes) != hipSuccess) {
+            p = nullptr;
+            (void)hipGetLastError();
+            return HSS_ENOMEM;
+        }
+        bytes = nbytes;
+        return HSS_OK;
+    }
+    template <class T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Upload arena for small descriptor tables: pinned host staging + device mirror.  push() copies
+// a table into the staging area and enqueues an async H2D copy; the returned device pointer is
+// valid for kernels enqueued afterwards on the same stream.  reset() may be called only after
+// the stream has been synchronised.
+struct DescArena {
+    char*  h = nullptr;
+    char*  d = nullptr;
+    size_t cap = 0, used = 0;
+    ~DescArena() { release(); }
+    void release() {
+        if (h) (void)hipHostFree(h);
+        if (d) (void)hipFree(d);
+        h = d = nullptr;
+        cap = used = 0;
+    }
+    int init(size_t bytes) {
+        release();
+        if (hipHostMalloc((void**)&h, bytes, hipHostMallocDefault) != hipSuccess) return HSS_ENOMEM;
+        if (hipMalloc((void**)&d, bytes) != hipSuccess) return HSS_ENOMEM;
+        cap = bytes;
+        used = 0;
+        return HSS_OK;
+    }
+    void reset() { used = 0; }
+    // returns device pointer or nullptr when full
+    void* push(const void* src, size_t bytes, hipStream_t st) {
+        size_t off = (used + 255) & ~size_t(255);
+        if (off + bytes > cap) return nullptr;
+        memcpy(h + off, src, bytes);
+        if (hipMemcpyAsync(d + off, h + off, bytes, hipMemcpyHostToDevice, st) != hipSuccess) return nullptr;
+        used = off + bytes;
+        return d + off;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Batched ragged GEMM on the FP64 matrix cores:  C = alpha * op(A) * op(B) + beta * C  per item.
+// All matrices row-major.  op(A) is M x K, op(B) is K x N, C is M x N.  Items with M, N or K == 0
+// are legal (K == 0 scales C by beta).
+struct GemmItem {
+    const double* A;
+    const double* B;
+    double*       C;
+    int32_t M, N, K;
+    int32_t lda, ldb, ldc;
+};
+int bgemm(hipStream_t st, const GemmItem* items_dev, int nitems, int maxM, int maxN, bool transA, bool transB,
+          double alpha, double beta);
+
+// ---------------------------------------------------------------------------------------------
+// Sampling S = K(Fp,Fp) * Omega (fused Gram + exp + contraction on the matrix cores).
+// Fp: n_pad x r_pad (zero padded), nu: n_pad squared norms, Om/S: n_pad x s_pad, n_pad % 256 == 0,
+// r_pad % 4 == 0 (<= 96), s_pad % 128 == 0.
+int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S,
+                  int64_t n_pad, int r_pad, int s_pad, double h);
+int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad);
+// Fp[i, :] = F[perm[i], :] zero padded to r_pad columns; rows >= n are zeroed.  perm == nullptr: identity.
+int gather_pad_rows_launch(hipStream_t st, const double* F, const int64_t* perm, double* Fp, int64_t n, int64_t n_pad,
+                           int r, int r_pad);
+// Omega (n_pad x s_pad): standard normals for rows < n and columns < s, zeros elsewhere.
+int omega_fill_launch(hipStream_t st, double* Om, int64_t n, int64_t n_pad, int s, int s_pad, uint64_t seed);

@@ -1,0 +1,76 @@
+// The context behind the opaque hss_ctx handle: options, the cluster tree, the HSS generators, the ULV
+// factors and the fixed work vectors of the solve / mat-vec / ADMM loop.
+#pragma once
+#include "common.h"
+#include "dense.h"
+#include "levels.h"
+#include "rowid.h"
+#include "solve.h"
+#include "vec.h"
+#include <new>
+#include <string>
+
+struct Level {
+    int N = 0;                              // nodes at this level (2^l)
+    std::vector<int> msz, rk;               // node sizes and ranks (rk = 0 at the root)
+    std::vector<int64_t> moff, koff;        // prefix sums of msz, rk              [N+1]
+    std::vector<int64_t> uoff, boff;        // prefix sums of msz*rk, k_a*k_b       [N+1]
+    int maxm = 0, maxk = 0;
+    DevBuf d_moff, d_koff, d_uoff;          // device copies of the prefix sums
+    // generators
+    DevBuf U;                               // (msz x rk) row-major per node, at uoff
+    DevBuf J;                               // int32 skeleton rows (local), at koff
+    DevBuf skel;                            // int64 skeleton points (cluster-tree order), at koff
+    DevBuf B;                               // (k_a x k_b) per inner node, at boff
+    // ULV factors
+    std::vector<char> pass;                 // 1: rank == size, nothing eliminated at this node
+    std::vector<int64_t> foff;              // prefix sums of msz*msz over eliminated nodes (0 for pass nodes)
+    DevBuf Mup, Mdown;                      // dense operators of the up / down sweep
+    std::vector<int64_t> kkoff;             // prefix sums of rk*rk
+    DevBuf RT, RTi;                         // R^T and R^-T per node (k x k), R = reduced basis handed to the parent
+    // solve plumbing
+    DevBuf bvec, ce, xvec;                  // level vectors: input (sum msz), eliminated part (sum msz-rk), output (sum msz)
+    DevBuf up_items, down_items, work;      // SolveItem tables and the (node, row block) work list
+    int nwork = 0;
+    // mat-vec plumbing
+    DevBuf xt, g;                           // (sum rk) each
+    DevBuf mv_up, mv_dn_u, mv_dn_b, mv_dn_bt, mv_leaf_d;   // GemvItem tables
+    int n_dn_b = 0;
+};
+
+struct hss_ctx {
+    hipStream_t stream = nullptr;
+    // options
+    int64_t opt_s = 128, opt_p = 10, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;
+    double  opt_abs_tol = 1e-8;
+    // problem
+    bool compressed = false, factored = false;
+    int64_t n = 0, n_pad = 0;
+    int r = 0, r_pad = 0, leaf = 0, L = 0, s = 0, s_pad = 0, kcap = 0;
+    double h = 0.0, tol = 0.0, delta = 0.0, beta = -1.0;
+    int warnings = 0;
+    DevBuf Fp, nu, yp, perm, Dleaf;
+    std::vector<int64_t> perm_host;
+    std::vector<Level> lev;                 // 0 .. L
+    DevBuf rootinv;                         // inverse of the root block (root_m x root_m)
+    int root_m = 0;
+    DevBuf flags;                           // int[4] device flags (bit 0: tiny pivot)
+    DescArena arena;
+    // fixed vectors (cluster-tree order)
+    DevBuf mv_x, mv_y;                      // mat-vec in / out
+    DevBuf v_x, v_z, v_mu, v_t, v_w, v_e, v_u;   // ADMM
+    DevBuf partial, scal;                   // reduction partials (4*VEC_BLOCKS), device scalars (16)
+    // stats
+    double sample_flops = 0.0, t_tree = 0.0, t_sample = 0.0, t_levels = 0.0, t_guard = 0.0, t_factor = 0.0;
+    int64_t generator_bytes = 0, factor_bytes = 0, factor_bytes_compact = 0;
+};
+
+int build_cluster_tree(const double* F_host, int64_t n, int r, int leaf, int64_t* perm);
+
+// hss.hip
+int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
+                      const double* Omega, int s_in);
+int hss_matvec_perm(hss_ctx* c);           // mv_y = K~' mv_x  (cluster-tree order, shift included)
+// ulv.hip
+int ulv_factor_impl(hss_ctx* c, double beta);
+int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm);   // cluster-tree order; may alias

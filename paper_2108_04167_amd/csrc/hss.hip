@@ -1,0 +1,431 @@
+// HSS compression of the Gaussian kernel matrix (Algorithm 3, first line), level by level up the
+// cluster tree, the HSS mat-vec, the definiteness guard and the export of the generators.
+//
+//   leaf t:    D_t = K(I_t, I_t);  S_t = S(I_t,:) - D_t Omega(I_t,:);  row ID  S_t ~= U_t S_t(J_t,:)
+//   inner t:   B_ab = K(skel_a, skel_b);  S_t = [S~_a - B_ab Om~_b; S~_b - B_ab^T Om~_a];  row ID (not at the root)
+//   S~_t = S_t(J_t,:),  Om~_t = U_t^T [Om~_a; Om~_b]
+// Every step is a batched launch over all nodes of a level; only the ranks come back to the host (one
+// small copy per level) to size the next level.
+#include "ctx.h"
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+
+namespace {
+
+double wall() {
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+template <class T>
+int upload(hss_ctx* c, DevBuf& buf, const std::vector<T>& v) {
+    HSS_TRY(buf.reserve(sizeof(T) * std::max<size_t>(v.size(), 1)));
+    if (!v.empty()) HIP_TRY(hipMemcpyAsync(buf.p, v.data(), sizeof(T) * v.size(), hipMemcpyHostToDevice, c->stream));
+    return HSS_OK;
+}
+
+// smallest eigenvalue of the symmetric tridiagonal matrix (a: diagonal, b: off-diagonal) by bisection on
+// the Sturm count
+double tridiag_min_eig(const std::vector<double>& a, const std::vector<double>& b) {
+    const int m = (int)a.size();
+    double lo = a[0], hi = a[0];
+    for (int i = 0; i < m; ++i) {
+        double rad = (i > 0 ? std::fabs(b[i - 1]) : 0.0) + (i + 1 < m ? std::fabs(b[i]) : 0.0);
+        lo = std::min(lo, a[i] - rad);
+        hi = std::max(hi, a[i] + rad);
+    }
+    auto count_below = [&](double x) {   // number of eigenvalues < x
+        int cnt = 0;
+        double d = 1.0;
+        for (int i = 0; i < m; ++i) {
+            double off = i > 0 ? b[i - 1] * b[i - 1] : 0.0;
+            d = a[i] - x - (i > 0 ? off / d : 0.0);
+            if (d == 0.0) d = 1e-300;
+            if (d < 0.0) ++cnt;
+        }
+        return cnt;
+    };
+    for (int it = 0; it < 200 && hi - lo > 1e-14 * std::max(1.0, std::fabs(lo) + std::fabs(hi)); ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (count_below(mid) >= 1) hi = mid;
+        else lo = mid;
+    }
+    return 0.5 * (lo + hi);
+}
+
+int build_matvec_tables(hss_ctx* c) {
+    hipStream_t st = c->stream;
+    const int L = c->L;
+    HSS_TRY(c->mv_x.reserve(sizeof(double) * c->n));
+    HSS_TRY(c->mv_y.reserve(sizeof(double) * c->n));
+    double* mvx = c->mv_x.as<double>();
+    double* mvy = c->mv_y.as<double>();
+    for (int l = 1; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        HSS_TRY(lv.xt.reserve(sizeof(double) * std::max<int64_t>(lv.koff[lv.N], 1)));
+        HSS_TRY(lv.g.reserve(sizeof(double) * std::max<int64_t>(lv.koff[lv.N], 1)));
+    }
+    for (int l = L; l >= 1; --l) {
+        Level& lv = c->lev[l];
+        const double* xin = (l == L) ? mvx : c->lev[l + 1].xt.as<double>();
+        std::vector<GemvItem> up(lv.N), dn(lv.N);
+        for (int t = 0; t < lv.N; ++t) {
+            const double* U = lv.U.as<double>() + lv.uoff[t];
+            up[t] = GemvItem{U, xin + lv.moff[t], lv.xt.as<double>() + lv.koff[t], lv.msz[t], lv.rk[t], lv.rk[t], 0};
+            // down: (node's rows) = U_t g_t, written where the children's g live (leaf: added to y)
+            double* dst = (l == L) ? mvy + lv.moff[t] : c->lev[l + 1].g.as<double>() + lv.moff[t];
+            dn[t] = GemvItem{U, lv.g.as<double>() + lv.koff[t], dst, lv.msz[t], lv.rk[t], lv.rk[t], 0};
+        }
+        HSS_TRY(upload(c, lv.mv_up, up));
+        HSS_TRY(upload(c, lv.mv_dn_u, dn));
+        // coupling through the parent's B: g_a (+)= B xt_b, g_b (+)= B^T xt_a
+        Level& pl = c->lev[l - 1];
+        std::vector<GemvItem> b1(pl.N), b2(pl.N);
+        for (int i = 0; i < pl.N; ++i) {
+            const int a = 2 * i, b = 2 * i + 1;
+            const double* B = pl.B.as<double>() + pl.boff[i];
+            b1[i] = GemvItem{B, lv.xt.as<double>() + lv.koff[b], lv.g.as<double>() + lv.koff[a], lv.rk[a], lv.rk[b], lv.rk[b], 0};
+            b2[i] = GemvItem{B, lv.xt.as<double>() + lv.koff[a], lv.g.as<double>() + lv.koff[b], lv.rk[a], lv.rk[b], lv.rk[b], 0};
+        }
+        HSS_TRY(upload(c, lv.mv_dn_b, b1));
+        HSS_TRY(upload(c, lv.mv_dn_bt, b2));
+        lv.n_dn_b = pl.N;
+    }
+    Level& leafl = c->lev[L];
+    std::vector<GemvItem> dd(leafl.N);
+    for (int t = 0; t < leafl.N; ++t)
+        dd[t] = GemvItem{c->Dleaf.as<double>() + (size_t)t * c->leaf * c->leaf, mvx + (size_t)t * c->leaf,
+                         mvy + (size_t)t * c->leaf, c->leaf, c->leaf, c->leaf, 0};
+    HSS_TRY(upload(c, leafl.mv_leaf_d, dd));
+    HIP_TRY(hipStreamSynchronize(st));   // the host vectors above go out of scope
+    return HSS_OK;
+}
+
+}  // namespace
+
+// mv_y = (K~ + delta I) mv_x, cluster-tree order (two-pass HSS product).
+int hss_matvec_perm(hss_ctx* c) {
+    hipStream_t st = c->stream;
+    const int L = c->L;
+    double* mvx = c->mv_x.as<double>();
+    double* mvy = c->mv_y.as<double>();
+    for (int l = L; l >= 1; --l) {
+        Level& lv = c->lev[l];
+        HSS_TRY(bgemv_launch(st, lv.mv_up.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, true, 1.0, 0.0));
+    }
+    for (int l = 1; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        // contribution handed down by the parent level (written by the parent's U g), then the coupling
+        const double beta = (l == 1) ? 0.0 : 1.0;
+        HSS_TRY(bgemv_launch(st, lv.mv_dn_b.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, false, 1.0, beta));
+        HSS_TRY(bgemv_launch(st, lv.mv_dn_bt.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, true, 1.0, beta));
+        if (l < L) HSS_TRY(bgemv_launch(st, lv.mv_dn_u.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, false, 1.0, 0.0));
+    }
+    Level& leafl = c->lev[L];
+    HSS_TRY(bgemv_launch(st, leafl.mv_leaf_d.as<GemvItem>(), leafl.N, c->leaf, c->leaf, false, 1.0, 0.0));
+    if (L >= 1) HSS_TRY(bgemv_launch(st, leafl.mv_dn_u.as<GemvItem>(), leafl.N, leafl.maxm, leafl.maxk, false, 1.0, 1.0));
+    if (c->delta != 0.0) HSS_TRY(vec_axpby(st, mvy, mvx, c->delta, 1.0, c->n));
+    return HSS_OK;
+}
+
+namespace {
+
+// delta = 1.1 * max(0, -lambda_min(K~)) from a Lanczos run on the HSS mat-vec (no re-orthogonalisation:
+// only the extreme Ritz value is used).
+int definiteness_guard(hss_ctx* c) {
+    hipStream_t st = c->stream;
+    const int64_t n = c->n;
+    c->delta = 0.0;
+    const int iters = (int)std::min<int64_t>(n, 64);
+    DevBuf vprev, vcur;
+    HSS_TRY(vprev.reserve(sizeof(double) * n));
+    HSS_TRY(vcur.reserve(sizeof(double) * n));
+    std::vector<double> v0(n);
+    uint64_t sd = 0x9E3779B97F4A7C15ull ^ (uint64_t)c->opt_seed;
+    double nrm = 0.0;
+    for (int64_t i = 0; i < n; ++i) {   // splitmix64 -> uniform(-1, 1)
+        sd += 0x9E3779B97F4A7C15ull;
+        uint64_t z = sd;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        v0[i] = (double)(z >> 11) * (2.0 / 9007199254740992.0) - 1.0;
+        nrm += v0[i] * v0[i];
+    }
+    nrm = std::sqrt(nrm);
+    for (auto& x : v0) x /= nrm;
+    HIP_TRY(hipMemcpyAsync(vcur.p, v0.data(), sizeof(double) * n, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemsetAsync(vprev.p, 0, sizeof(double) * n, st));
+    double* part = c->partial.as<double>();
+    double* scal = c->scal.as<double>();
+    double* w = c->mv_y.as<double>();
+    std::vector<double> alpha, beta;
+    double bprev = 0.0;
+    for (int j = 0; j < iters; ++j) {
+        HIP_TRY(hipMemcpyAsync(c->mv_x.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
+        HSS_TRY(hss_matvec_perm(c));
+        HSS_TRY(vec_dot(st, w, vcur.as<double>(), n, part, scal));
+        double a;
+        HIP_TRY(hipMemcpyAsync(&a, scal, sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        alpha.push_back(a);
+        HSS_TRY(vec_lanczos_update(st, w, vcur.as<double>(), vprev.as<double>(), a, bprev, n));
+        HSS_TRY(vec_dot(st, w, w, n, part, scal));
+        double b2;
+        HIP_TRY(hipMemcpyAsync(&b2, scal, sizeof(double), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        const double b = std::sqrt(b2 > 0.0 ? b2 : 0.0);
+        if (!(b > 1e-12 * std::max(1.0, std::fabs(a))) || j + 1 == iters) break;
+        beta.push_back(b);
+        // vprev <- vcur, vcur <- w / b
+        HIP_TRY(hipMemcpyAsync(vprev.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
+        HSS_TRY(vec_axpby(st, vcur.as<double>(), w, 1.0 / b, 0.0, n));
+        bprev = b;
+    }
+    beta.resize(alpha.size() > 0 ? alpha.size() - 1 : 0);
+    const double lam = tridiag_min_eig(alpha, beta);
+    if (lam < 0.0) {
+        c->delta = 1.1 * (-lam);
+        c->warnings |= HSS_WSHIFT;
+    }
+    return HSS_OK;
+}
+
+}  // namespace
+
+int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
+                      const double* Omega, int s_in) {
+    if (!c || !F || !y) return HSS_EINVAL;
+    if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol < 1.0)) return HSS_EINVAL;
+    if (leaf < 16 || leaf % 16 != 0 || n % leaf != 0) return HSS_EINVAL;
+    const int64_t nl = n / leaf;
+    if (nl & (nl - 1)) return HSS_EINVAL;
+    if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
+    const int s = Omega ? s_in : (int)c->opt_s;
+    if (s < 1) return HSS_EINVAL;
+    const int s_pad = (int)round_up(s, 128);
+    if (s_pad > 512) return HSS_EUNSUPPORTED;
+    int64_t kcap = c->opt_max_rank > 0 ? c->opt_max_rank : (int64_t)s - c->opt_p;
+    if (kcap > s) kcap = s;
+    if (kcap < 1) return HSS_EINVAL;
+    if (kcap > 512) return HSS_EUNSUPPORTED;
+    int L = 0;
+    while ((int64_t(1) << L) < nl) ++L;
+
+    hipStream_t st = c->stream;
+    c->compressed = c->factored = false;
+    c->lev.clear();
+    c->lev.resize(L + 1);
+    c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
+    c->h = h; c->tol = tol; c->delta = 0.0; c->beta = -1.0; c->warnings = 0;
+    c->r_pad = (int)round_up(r, 4);
+    c->n_pad = round_up(n, 256);
+    const int r_pad = c->r_pad;
+    const int64_t n_pad = c->n_pad;
+    if (!c->arena.h) HSS_TRY(c->arena.init(size_t(96) << 20));
+    c->arena.reset();
+    HSS_TRY(c->flags.reserve(sizeof(int) * 4));
+    HIP_TRY(hipMemsetAsync(c->flags.p, 0, sizeof(int) * 4, st));
+    HSS_TRY(c->partial.reserve(sizeof(double) * 4 * VEC_BLOCKS));
+    HSS_TRY(c->scal.reserve(sizeof(double) * 16));
+
+    // ---- labels must be +-1; cluster tree on the host ----
+    double t0 = wall();
+    std::vector<double> Fh((size_t)n * r), yh(n);
+    HIP_TRY(hipMemcpyAsync(Fh.data(), F, sizeof(double) * n * r, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(yh.data(), y, sizeof(double) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int64_t i = 0; i < n; ++i)
+        if (yh[i] != 1.0 && yh[i] != -1.0) return HSS_EINVAL;
+    c->perm_host.resize(n);
+    HSS_TRY(build_cluster_tree(Fh.data(), n, r, leaf, c->perm_host.data()));
+    HSS_TRY(c->perm.reserve(sizeof(int64_t) * n));
+    HIP_TRY(hipMemcpyAsync(c->perm.p, c->perm_host.data(), sizeof(int64_t) * n, hipMemcpyHostToDevice, st));
+    const int64_t* perm = c->perm.as<int64_t>();
+    HSS_TRY(c->Fp.reserve(sizeof(double) * n_pad * r_pad));
+    HSS_TRY(c->nu.reserve(sizeof(double) * n_pad));
+    HSS_TRY(c->yp.reserve(sizeof(double) * n));
+    HSS_TRY(gather_pad_rows_launch(st, F, perm, c->Fp.as<double>(), n, n_pad, r, r_pad));
+    HSS_TRY(row_norms_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, r_pad));
+    HSS_TRY(vec_gather(st, c->yp.as<double>(), y, perm, n));
+    HIP_TRY(hipStreamSynchronize(st));
+    c->t_tree = wall() - t0;
+
+    // ---- sampling ----
+    DevBuf S0, S1, Om0, Om1, Wk;
+    const size_t nsbytes = sizeof(double) * (size_t)n_pad * s_pad;
+    HSS_TRY(S0.reserve(nsbytes));
+    HSS_TRY(Om0.reserve(nsbytes));
+    t0 = wall();
+    if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Om0.as<double>(), n, n_pad, s, s_pad));
+    else HSS_TRY(omega_fill_launch(st, Om0.as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
+    HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Om0.as<double>(), S0.as<double>(), n_pad, r_pad,
+                          s_pad, h));
+    HIP_TRY(hipStreamSynchronize(st));
+    c->t_sample = wall() - t0;
+    c->sample_flops = 2.0 * (double)n * (double)n * (double)(s + r);
+
+    // ---- leaf level: D_t and S_t = S - D Omega ----
+    t0 = wall();
+    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)n * leaf));
+    {
+        Level& lv = c->lev[L];
+        lv.N = (int)nl;
+        lv.msz.assign(lv.N, leaf);
+        lv.moff.resize(lv.N + 1);
+        for (int t = 0; t <= lv.N; ++t) lv.moff[t] = (int64_t)t * leaf;
+        lv.maxm = leaf;
+        std::vector<KBItem> kb(lv.N);
+        std::vector<GemmItem> gm(lv.N);
+        for (int t = 0; t < lv.N; ++t) {
+            double* D = c->Dleaf.as<double>() + (size_t)t * leaf * leaf;
+            kb[t] = KBItem{nullptr, nullptr, (int64_t)t * leaf, (int64_t)t * leaf, D, leaf, leaf, leaf, 0};
+            gm[t] = GemmItem{D, Om0.as<double>() + (size_t)t * leaf * s_pad, S0.as<double>() + (size_t)t * leaf * s_pad,
+                             leaf, s_pad, leaf, leaf, s_pad, s_pad};
+        }
+        HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
+        if (L >= 1) HSS_TRY(bgemm_host(st, c->arena, gm, false, false, -1.0, 1.0));
+    }
+    if (L >= 1) {
+        HSS_TRY(S1.reserve(nsbytes));
+        HSS_TRY(Om1.reserve(nsbytes));
+        HSS_TRY(Wk.reserve(nsbytes));
+    }
+    const int kc = (int)kcap;
+    DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, rowmap;
+    if (L >= 1) {
+        HSS_TRY(Lc.reserve(sizeof(double) * (size_t)n * kc));
+        HSS_TRY(norms0.reserve(sizeof(double) * n));
+        HSS_TRY(norms1.reserve(sizeof(double) * n));
+        HSS_TRY(sel.reserve(sizeof(int) * n));
+        HSS_TRY(jtmp.reserve(sizeof(int) * (size_t)nl * kc));
+        HSS_TRY(rkd.reserve(sizeof(int) * nl));
+        HSS_TRY(done.reserve(sizeof(int) * nl));
+        HSS_TRY(r11.reserve(sizeof(double) * nl));
+        HSS_TRY(rowmap.reserve(sizeof(int64_t) * n));
+    }
+    double* Acur = S0.as<double>();
+    double* Anext = S1.as<double>();
+    double* Ocur = Om0.as<double>();
+    double* Onext = Om1.as<double>();
+    int64_t rank_sum = 0;
+    for (int l = L; l >= 1; --l) {
+        Level& lv = c->lev[l];
+        const int N = lv.N;
+        const int64_t rows = lv.moff[N];
+        HSS_TRY(upload(c, lv.d_moff, lv.moff));
+        // interpolative decompositions of all nodes of the level, on a work copy of the sample rows
+        HIP_TRY(hipMemcpyAsync(Wk.p, Acur, sizeof(double) * (size_t)rows * s_pad, hipMemcpyDeviceToDevice, st));
+        IdLevelArgs ia;
+        ia.W = Wk.as<double>(); ia.ld = s_pad; ia.moff = lv.d_moff.as<int64_t>(); ia.kcap = (int)kcap; ia.kc = kc;
+        ia.rows_per_block = 32; ia.rel = tol / 10.0; ia.abs_tol = c->opt_abs_tol;
+        ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>(); ia.rk = rkd.as<int>();
+        ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>();
+        HSS_TRY(id_init(st, ia, rows, N, norms0.as<double>()));
+        HSS_TRY(id_steps(st, ia, N, lv.maxm, norms0.as<double>(), norms1.as<double>()));
+        lv.rk.resize(N);
+        HIP_TRY(hipMemcpyAsync(lv.rk.data(), rkd.p, sizeof(int) * N, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        c->arena.reset();
+        lv.koff.assign(N + 1, 0);
+        lv.uoff.assign(N + 1, 0);
+        lv.maxk = 0;
+        for (int t = 0; t < N; ++t) {
+            const int k = lv.rk[t];
+            if (k < 1 || k > lv.msz[t]) return HSS_EHIP;   // the kernels guarantee 1 <= k <= size
+            lv.koff[t + 1] = lv.koff[t] + k;
+            lv.uoff[t + 1] = lv.uoff[t] + (int64_t)k * lv.msz[t];
+            lv.maxk = std::max(lv.maxk, k);
+            if (k == kcap && k < lv.msz[t]) c->warnings |= HSS_WRANK;
+            rank_sum += k;
+        }
+        const int64_t ktot = lv.koff[N];
+        HSS_TRY(upload(c, lv.d_koff, lv.koff));
+        HSS_TRY(upload(c, lv.d_uoff, lv.uoff));
+        HSS_TRY(lv.U.reserve(sizeof(double) * lv.uoff[N]));
+        HSS_TRY(lv.J.reserve(sizeof(int) * ktot));
+        HSS_TRY(lv.skel.reserve(sizeof(int64_t) * ktot));
+        HSS_TRY(id_finish(st, ia, N, lv.maxm, lv.d_koff.as<int64_t>(), lv.d_uoff.as<int64_t>(), lv.U.as<double>(),
+                          lv.J.as<int>()));
+        HSS_TRY(rowmap_launch(st, lv.d_moff.as<int64_t>(), lv.d_koff.as<int64_t>(), jtmp.as<int>(), kc, N,
+                              rowmap.as<int64_t>()));
+        HSS_TRY(gather_index_launch(st, lv.skel.as<int64_t>(), l == L ? nullptr : c->lev[l + 1].skel.as<int64_t>(),
+                                    rowmap.as<int64_t>(), ktot));
+        // parent level
+        Level& pl = c->lev[l - 1];
+        pl.N = N / 2;
+        pl.msz.resize(pl.N);
+        pl.moff.assign(pl.N + 1, 0);
+        pl.boff.assign(pl.N + 1, 0);
+        pl.maxm = 0;
+        for (int i = 0; i < pl.N; ++i) {
+            pl.msz[i] = lv.rk[2 * i] + lv.rk[2 * i + 1];
+            pl.moff[i + 1] = pl.moff[i] + pl.msz[i];
+            pl.boff[i + 1] = pl.boff[i] + (int64_t)lv.rk[2 * i] * lv.rk[2 * i + 1];
+            pl.maxm = std::max(pl.maxm, pl.msz[i]);
+        }
+        HSS_TRY(pl.B.reserve(sizeof(double) * pl.boff[pl.N]));
+        std::vector<KBItem> kb(pl.N);
+        for (int i = 0; i < pl.N; ++i) {
+            const int a = 2 * i, b = 2 * i + 1;
+            kb[i] = KBItem{lv.skel.as<int64_t>() + lv.koff[a], lv.skel.as<int64_t>() + lv.koff[b], 0, 0,
+                           pl.B.as<double>() + pl.boff[i], lv.rk[a], lv.rk[b], lv.rk[b], 0};
+        }
+        HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
+        if (l - 1 >= 1) {
+            // S~ = S_t(J,:) and Om~ = U^T Om_t, laid out as the parent's rows
+            HSS_TRY(copy_rows_launch(st, Anext, s_pad, Acur, s_pad, rowmap.as<int64_t>(), ktot, s_pad));
+            std::vector<GemmItem> g1(N);
+            for (int t = 0; t < N; ++t)
+                g1[t] = GemmItem{lv.U.as<double>() + lv.uoff[t], Ocur + (size_t)lv.moff[t] * s_pad,
+                                 Onext + (size_t)lv.koff[t] * s_pad, lv.rk[t], s_pad, lv.msz[t], lv.rk[t], s_pad, s_pad};
+            HSS_TRY(bgemm_host(st, c->arena, g1, true, false, 1.0, 0.0));
+            // parent sample rows: [S~_a - B Om~_b; S~_b - B^T Om~_a]
+            std::vector<GemmItem> g2(pl.N), g3(pl.N);
+            for (int i = 0; i < pl.N; ++i) {
+                const int a = 2 * i, b = 2 * i + 1;
+                const double* B = pl.B.as<double>() + pl.boff[i];
+                g2[i] = GemmItem{B, Onext + (size_t)lv.koff[b] * s_pad, Anext + (size_t)lv.koff[a] * s_pad,
+                                 lv.rk[a], s_pad, lv.rk[b], lv.rk[b], s_pad, s_pad};
+                g3[i] = GemmItem{B, Onext + (size_t)lv.koff[a] * s_pad, Anext + (size_t)lv.koff[b] * s_pad,
+                                 lv.rk[b], s_pad, lv.rk[a], lv.rk[b], s_pad, s_pad};
+            }
+            HSS_TRY(bgemm_host(st, c->arena, g2, false, false, -1.0, 1.0));
+            HSS_TRY(bgemm_host(st, c->arena, g3, true, false, -1.0, 1.0));
+            std::swap(Acur, Anext);
+            std::swap(Ocur, Onext);
+        }
+    }
+    // root bookkeeping
+    {
+        Level& rl = c->lev[0];
+        if (L == 0) {
+            rl.N = 1;
+            rl.msz.assign(1, leaf);
+            rl.moff = {0, leaf};
+            rl.maxm = leaf;
+        }
+        rl.rk.assign(1, 0);
+        rl.koff = {0, 0};
+        rl.uoff = {0, 0};
+        rl.maxk = 0;
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    c->arena.reset();
+    c->t_levels = wall() - t0;
+
+    c->generator_bytes = (int64_t)sizeof(double) * n * leaf;
+    for (int l = 0; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        if (l >= 1) c->generator_bytes += (int64_t)sizeof(double) * lv.uoff[lv.N];
+        if (l < L) c->generator_bytes += (int64_t)sizeof(double) * lv.boff[lv.N];
+    }
+    (void)rank_sum;
+    HSS_TRY(build_matvec_tables(c));
+    c->compressed = true;
+    t0 = wall();
+    if (c->opt_guard && L >= 1) HSS_TRY(definiteness_guard(c));
+    HIP_TRY(hipStreamSynchronize(st));
+    c->t_guard = wall() - t0;
+    return c->warnings;
+}

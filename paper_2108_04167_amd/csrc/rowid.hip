@@ -1,0 +1,251 @@
+// Batched row interpolative decomposition  A_t ~= U_t A_t(J_t, :)  of the sample blocks of all nodes
+// of one tree level (per-node truncation of the HSS blocks, end of Sec. 3.2).
+//
+// Row-pivoted modified Gram-Schmidt, one kernel launch per pivot step for the whole level:
+//   step j, node t:  p = argmax_i ||a_i||  over rows not yet chosen;  stop when
+//                    ||a_p|| <= max(rel * ||a_p0||, abs) or j reaches the rank cap;
+//                    q = a_p / ||a_p||;  every other live row:  r_ij = a_i . q,  a_i -= r_ij q,
+//                    and its norm is recomputed from the updated row (no down-dating).
+// Every workgroup of a node recomputes the argmax from the node's norm array (<= 1024 values), so no
+// grid-wide synchronisation is needed; norms are double buffered between steps.  The coefficients
+// r_ij form [L11; L21] (rows in pivot order / the rest), and T = L21 L11^{-1} gives
+// U = P [I; T].  A node always keeps at least one row (rank >= 1).
+#include "common.h"
+#include "rowid.h"
+
+namespace {
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// norms0[i] = ||W_i||^2, sel[i] = 0.  One wavefront per row.
+__global__ __launch_bounds__(256) void id_init_kernel(const double* __restrict__ W, int ld, int64_t nrows,
+                                                      double* __restrict__ norms0, int* __restrict__ sel) {
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (row >= nrows) return;
+    double acc = 0.0;
+    for (int c = lane; c < ld; c += 64) {
+        double v = W[row * ld + c];
+        acc += v * v;
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        norms0[row] = acc;
+        sel[row] = 0;
+    }
+}
+
+template <int NPL>   // doubles per lane per row: ld == 64 * NPL
+__global__ __launch_bounds__(256) void id_step_kernel(IdLevelArgs a, int j, const double* __restrict__ nin,
+                                                      double* __restrict__ nout) {
+    const int node = blockIdx.x;
+    const int64_t m0 = a.moff[node];
+    const int msz = (int)(a.moff[node + 1] - m0);
+    const int lim = msz < a.kcap ? msz : a.kcap;
+    if (j >= lim || a.done[node]) return;
+    const int r0 = blockIdx.y * a.rows_per_block;
+    if (r0 >= msz) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // argmax of the live norms of this node (ties -> lowest row)
+    double bv = -2.0;
+    int bi = 0x7fffffff;
+    for (int i = tid; i < msz; i += 256) {
+        double v = nin[m0 + i];
+        if (v > bv) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        double ov = __shfl_xor(bv, off, 64);
+        int oi = __shfl_xor(bi, off, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    __shared__ double sv[4];
+    __shared__ int si[4];
+    if (lane == 0) { sv[wave] = bv; si[wave] = bi; }
+    __syncthreads();
+    bv = sv[0]; bi = si[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w)
+        if (sv[w] > bv || (sv[w] == bv && si[w] < bi)) { bv = sv[w]; bi = si[w]; }
+    if (bi >= msz) {   // no comparable norm (NaN input): stop this node
+        if (blockIdx.y == 0 && tid == 0) a.done[node] = 1;
+        return;
+    }
+    const int p = bi;
+    const double pv = sqrt(bv > 0.0 ? bv : 0.0);
+    const double r11 = (j == 0) ? pv : a.r11[node];
+    double thr = a.rel * r11;
+    if (a.abs_tol > thr) thr = a.abs_tol;
+    if (j > 0 && !(pv > thr)) {
+        if (blockIdx.y == 0 && tid == 0) a.done[node] = 1;
+        return;
+    }
+    if (blockIdx.y == 0 && tid == 0) {
+        a.jtmp[(size_t)node * a.kc + j] = p;
+        a.rk[node] = j + 1;
+        if (j == 0) a.r11[node] = pv;
+    }
+    const double inv = pv > 0.0 ? 1.0 / pv : 0.0;
+    double q[NPL];
+    {
+        const double* pr = a.W + (size_t)(m0 + p) * a.ld + lane;
+#pragma unroll
+        for (int u = 0; u < NPL; ++u) q[u] = pr[64 * u] * inv;
+    }
+    int rend = r0 + a.rows_per_block;
+    if (rend > msz) rend = msz;
+    for (int i = r0 + wave; i < rend; i += 4) {
+        const int64_t gi = m0 + i;
+        if (i == p) {
+            if (lane == 0) {
+                a.Lc[(size_t)gi * a.kc + j] = pv;
+                nout[gi] = -1.0;
+                a.sel[gi] = j + 1;
+            }
+            continue;
+        }
+        if (nin[gi] < 0.0) {
+            if (lane == 0) nout[gi] = -1.0;
+            continue;
+        }
+        double* ar = a.W + (size_t)gi * a.ld + lane;
+        double x[NPL];
+        double dot = 0.0;
+#pragma unroll
+        for (int u = 0; u < NPL; ++u) {
+            x[u] = ar[64 * u];
+            dot += x[u] * q[u];
+        }
+        dot = wave_sum(dot);
+        double nn = 0.0;
+#pragma unroll
+        for (int u = 0; u < NPL; ++u) {
+            x[u] -= dot * q[u];
+            nn += x[u] * x[u];
+            ar[64 * u] = x[u];
+        }
+        nn = wave_sum(nn);
+        if (lane == 0) {
+            a.Lc[(size_t)gi * a.kc + j] = dot;
+            nout[gi] = nn;
+        }
+    }
+}
+
+// T = L21 L11^{-1} row by row (one wavefront per row, the row's coefficients spread over the lanes),
+// and assembly of U (msz x k, row-major at uoff[node]) and of the compact skeleton list J.
+template <int KU>   // kc <= 64 * KU
+__global__ __launch_bounds__(256) void id_finish_kernel(IdLevelArgs a, const int64_t* __restrict__ koff,
+                                                        const int64_t* __restrict__ uoff, double* __restrict__ U,
+                                                        int* __restrict__ J) {
+    const int node = blockIdx.x;
+    const int64_t m0 = a.moff[node];
+    const int msz = (int)(a.moff[node + 1] - m0);
+    const int k = a.rk[node];
+    const int r0 = blockIdx.y * a.rows_per_block;
+    if (r0 >= msz) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int* jt = a.jtmp + (size_t)node * a.kc;
+    if (blockIdx.y == 0)
+        for (int c = tid; c < k; c += 256) J[koff[node] + c] = jt[c];
+    double* Un = U + uoff[node];
+    int rend = r0 + a.rows_per_block;
+    if (rend > msz) rend = msz;
+    for (int i = r0 + wave; i < rend; i += 4) {
+        const int64_t gi = m0 + i;
+        double* urow = Un + (size_t)i * k;
+        const int s = a.sel[gi];
+        if (s > 0) {
+            for (int c = lane; c < k; c += 64) urow[c] = (c == s - 1) ? 1.0 : 0.0;
+            continue;
+        }
+        double l[KU];
+        const double* lr = a.Lc + (size_t)gi * a.kc;
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            int c = lane + 64 * u;
+            l[u] = c < k ? lr[c] : 0.0;
+        }
+        // back substitution  t L11 = l,  columns from k-1 down to 0; L11[j][c] = Lc[row of pivot j][c], c <= j
+#pragma unroll
+        for (int uu = 0; uu < KU; ++uu) {
+            const int u = KU - 1 - uu;
+            if (64 * u >= k) continue;
+            for (int jj = 63; jj >= 0; --jj) {
+                const int j = 64 * u + jj;
+                if (j >= k) continue;
+                const double* Lj = a.Lc + (size_t)(m0 + jt[j]) * a.kc;
+                const double diag = Lj[j];
+                double tj = __shfl(l[u], jj, 64);
+                tj = diag != 0.0 ? tj / diag : 0.0;
+                if (lane == jj) l[u] = tj;
+#pragma unroll
+                for (int w = 0; w < KU; ++w) {
+                    if (w <= u) {
+                        int c = lane + 64 * w;
+                        if (c < j) l[w] -= tj * Lj[c];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            int c = lane + 64 * u;
+            if (c < k) urow[c] = l[u];
+        }
+    }
+}
+
+}  // namespace
+
+int id_init(hipStream_t st, const IdLevelArgs& a, int64_t nrows, int nnodes, double* norms0) {
+    if (nrows <= 0) return HSS_OK;
+    HIP_TRY(hipMemsetAsync(a.Lc, 0, sizeof(double) * (size_t)nrows * a.kc, st));
+    HIP_TRY(hipMemsetAsync(a.rk, 0, sizeof(int) * (size_t)nnodes, st));
+    HIP_TRY(hipMemsetAsync(a.done, 0, sizeof(int) * (size_t)nnodes, st));
+    hipLaunchKernelGGL(id_init_kernel, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, st, a.W, a.ld, nrows, norms0,
+                       a.sel);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+
+int id_steps(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* norms0, double* norms1) {
+    const int steps = maxmsz < a.kcap ? maxmsz : a.kcap;
+    const unsigned yc = (unsigned)((maxmsz + a.rows_per_block - 1) / a.rows_per_block);
+    dim3 grid((unsigned)nnodes, yc);
+    for (int j = 0; j < steps; ++j) {
+        const double* nin = (j & 1) ? norms1 : norms0;
+        double* nout = (j & 1) ? norms0 : norms1;
+        switch (a.ld / 64) {
+            case 2: hipLaunchKernelGGL(id_step_kernel<2>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 4: hipLaunchKernelGGL(id_step_kernel<4>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 6: hipLaunchKernelGGL(id_step_kernel<6>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 8: hipLaunchKernelGGL(id_step_kernel<8>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            default: return HSS_EUNSUPPORTED;
+        }
+    }
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+
+int id_finish(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, const int64_t* koff, const int64_t* uoff,
+              double* U, int* J) {
+    const unsigned yc = (unsigned)((maxmsz + a.rows_per_block - 1) / a.rows_per_block);
+    dim3 grid((unsigned)nnodes, yc);
+    const int ku = (a.kc + 63) / 64;
+    switch (ku) {
+        case 1: hipLaunchKernelGGL(id_finish_kernel<1>, grid, dim3(256), 0, st, a, koff, uoff, U, J); break;
+        case 2: hipLaunchKernelGGL(id_finish_kernel<2>, grid, dim3(256), 0, st, a, koff, uoff, U, J); break;
+        case 3: case 4: hipLaunchKernelGGL(id_finish_kernel<4>, grid, dim3(256), 0, st, a, koff, uoff, U, J); break;
+        case 5: case 6: case 7: case 8:
+            hipLaunchKernelGGL(id_finish_kernel<8>, grid, dim3(256), 0, st, a, koff, uoff, U, J); break;
+        default: return HSS_EUNSUPPORTED;
+    }
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}

@@ -1,0 +1,25 @@
+// ULV solve / HSS mat-vec kernels (host entry points in solve.hip).
+#pragma once
+#include "common.h"
+
+constexpr int SOLVE_ROWS_PER_BLOCK = 32;
+
+struct SolveItem {           // y = M [in0(0:n0); in1(0:m-n0)];  y(0:nout0) -> out0, y(nout0:m) -> out1
+    const double* M;         // m x m row-major (ld); null = identity (nothing eliminated at this node)
+    const double* in0;
+    const double* in1;
+    double*       out0;
+    double*       out1;
+    int32_t m, ld, n0, nout0;
+};
+
+struct GemvItem {
+    const double* A;         // M x N row-major
+    const double* x;
+    double*       y;
+    int32_t M, N, lda, pad;
+};
+
+int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork);
+int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool trans, double alpha,
+                 double beta);

@@ -1,0 +1,31 @@
+// Vector kernels (host entry points in vec.hip).
+#pragma once
+#include "common.h"
+
+constexpr int VEC_BLOCKS = 1024;   // workgroups (and partial sums) of a reduction
+
+struct AdmmVecs {
+    double* x;
+    double* z;
+    double* mu;
+    double* rhs;        // right-hand side of the next solve, Y q (written)
+    const double* sol;  // solution of the last solve, K_beta^{-1} Y q (read)
+    const double* y;    // labels, cluster-tree order
+    const double* w;    // Y K_beta^{-1} e
+};
+
+int vec_blocks(int64_t n);
+int vec_gather(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n);
+int vec_scatter(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n);
+int vec_mul(hipStream_t st, double* dst, const double* a, const double* b, int64_t n);
+int vec_dot(hipStream_t st, const double* a, const double* b, int64_t n, double* partial_dev, double* out_dev);
+int vec_axpby(hipStream_t st, double* y, const double* x, double a, double b, int64_t n);
+int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, double alpha, double beta, int64_t n);
+int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, double* part_out);
+int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, double C, double beta, const double* w1_dev,
+              const double* part_in, double* part_out);
+int margin_indicator(hipStream_t st, const double* z, double C, double* ebar, int64_t n);
+int bias_sums(hipStream_t st, const double* z, const double* y, const double* u, const double* ebar, int64_t n,
+              double* partial_dev, double* out_dev);
+int decision_launch(hipStream_t st, const double* Fp, const double* zy, int64_t n, const double* G, int64_t n_test, int r,
+                    int r_pad, double h, double bias, double* dec);

@@ -1,0 +1,284 @@
+// Vector kernels: the per-iteration ADMM updates (Algorithm 2 / Algorithm 3 inner loop), deterministic
+// two-stage reductions (wavefront shuffles inside a workgroup, a fixed-order sum over workgroup
+// partials), permutation gathers, and the label-assignment kernel of Algorithm 3.
+//
+// All ADMM vectors live in cluster-tree order inside the library.  Scalars produced on the device
+// (w1 = e^T K_beta^{-1} e, w2 = w^T q) stay on the device: an iteration never synchronises with the host.
+#include "common.h"
+#include "vec.h"
+
+namespace {
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Sum over the workgroup (256 threads); result valid in every thread.
+__device__ __forceinline__ double block_sum(double v, double* sh /*[4]*/) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    return ((sh[0] + sh[1]) + sh[2]) + sh[3];
+}
+
+// Fixed-order sum of `count` partials (count <= VEC_BLOCKS), redundantly by every workgroup.
+__device__ __forceinline__ double sum_partials(const double* __restrict__ part, int count, double* sh) {
+    double v = 0.0;
+    for (int i = threadIdx.x; i < count; i += 256) v += part[i];
+    return block_sum(v, sh);
+}
+
+__global__ void gather_kernel(double* __restrict__ dst, const double* __restrict__ src, const int64_t* __restrict__ perm,
+                              int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[perm[i]];
+}
+__global__ void scatter_kernel(double* __restrict__ dst, const double* __restrict__ src, const int64_t* __restrict__ perm,
+                               int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[perm[i]] = src[i];
+}
+
+// partial[b] = sum over the workgroup's grid-stride slice of a[i]*b[i] (b == nullptr: of a[i])
+__global__ __launch_bounds__(256) void dot_partial_kernel(const double* __restrict__ a, const double* __restrict__ b,
+                                                          int64_t n, double* __restrict__ partial) {
+    __shared__ double sh[4];
+    double v = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        v += b ? a[i] * b[i] : a[i];
+    v = block_sum(v, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = v;
+}
+__global__ __launch_bounds__(256) void finish_sum_kernel(const double* __restrict__ partial, int count,
+                                                         double* __restrict__ out) {
+    __shared__ double sh[4];
+    double v = sum_partials(partial, count, sh);
+    if (threadIdx.x == 0) *out = v;
+}
+
+// w <- y .* wbar  (Algorithm 3: w = Y K_beta^{-1} e)
+__global__ void mul_kernel(double* __restrict__ dst, const double* __restrict__ a, const double* __restrict__ b, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = a[i] * b[i];
+}
+
+// Start of a run: x = z = mu = 0, q = e, rhs = Y q = y, partial sums of w^T q.
+__global__ __launch_bounds__(256) void admm_start_kernel(AdmmVecs v, int64_t n, double* __restrict__ part_out) {
+    __shared__ double sh[4];
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        v.x[i] = 0.0;
+        v.z[i] = 0.0;
+        v.mu[i] = 0.0;
+        v.rhs[i] = v.y[i];
+        acc += v.w[i];
+    }
+    acc = block_sum(acc, sh);
+    if (threadIdx.x == 0) part_out[blockIdx.x] = acc;
+}
+
+// One iteration after the solve: sol holds K_beta^{-1} Y q^k.
+//   x = Y sol - (w2 / w1) w;  z = clip(x - mu/beta, 0, C);  mu -= beta (x - z);
+//   q = e + mu + beta z;  rhs = Y q;  partial sums of w^T q for the next iteration.
+__global__ __launch_bounds__(256) void admm_step_kernel(AdmmVecs v, int64_t n, double C, double beta,
+                                                        const double* __restrict__ w1, const double* __restrict__ part_in,
+                                                        int nparts, double* __restrict__ part_out) {
+    __shared__ double sh[4];
+    const double w2 = sum_partials(part_in, nparts, sh);
+    const double ratio = w2 / (*w1);
+    const double ibeta = 1.0 / beta;
+    double acc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const double yi = v.y[i], wi = v.w[i];
+        const double mu = v.mu[i];
+        const double x = yi * v.sol[i] - ratio * wi;
+        double z = x - mu * ibeta;
+        z = z < 0.0 ? 0.0 : (z > C ? C : z);
+        const double mun = mu - beta * (x - z);
+        v.x[i] = x;
+        v.z[i] = z;
+        v.mu[i] = mun;
+        const double q = 1.0 + mun + beta * z;
+        v.rhs[i] = yi * q;
+        acc += wi * q;
+    }
+    acc = block_sum(acc, sh);
+    if (threadIdx.x == 0) part_out[blockIdx.x] = acc;
+}
+
+// ebar_i = 1 if 0 < z_i < C else 0
+__global__ void margin_kernel(const double* __restrict__ z, double C, double* __restrict__ ebar, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) ebar[i] = (z[i] > 0.0 && z[i] < C) ? 1.0 : 0.0;
+}
+// partials of  sum_M y_j,  sum_i y_i z_i u_i,  |M|
+__global__ __launch_bounds__(256) void bias_partial_kernel(const double* __restrict__ z, const double* __restrict__ y,
+                                                           const double* __restrict__ u, const double* __restrict__ ebar,
+                                                           int64_t n, double* __restrict__ partial /*[3][blocks]*/) {
+    __shared__ double sh[4];
+    double sy = 0.0, sz = 0.0, sc = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const double e = ebar[i];
+        sy += e * y[i];
+        sc += e;
+        sz += y[i] * z[i] * u[i];
+    }
+    sy = block_sum(sy, sh);
+    sz = block_sum(sz, sh);
+    sc = block_sum(sc, sh);
+    if (threadIdx.x == 0) {
+        partial[blockIdx.x] = sy;
+        partial[gridDim.x + blockIdx.x] = sz;
+        partial[2 * gridDim.x + blockIdx.x] = sc;
+    }
+}
+__global__ __launch_bounds__(256) void finish_sum3_kernel(const double* __restrict__ partial, int count,
+                                                          double* __restrict__ out /*[3]*/) {
+    __shared__ double sh[4];
+    for (int k = 0; k < 3; ++k) {
+        double v = sum_partials(partial + (size_t)k * count, count, sh);
+        if (threadIdx.x == 0) out[k] = v;
+    }
+}
+
+// y <- a*x + b*y;  y <- y + c*e? (generic helpers for the Lanczos recurrence of the definiteness guard)
+__global__ void axpby_kernel(double* __restrict__ y, const double* __restrict__ x, double a, double b, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) y[i] = a * x[i] + b * y[i];
+}
+// w <- w - alpha v - beta vprev
+__global__ void lanczos_update_kernel(double* __restrict__ w, const double* __restrict__ v, const double* __restrict__ vp,
+                                      double alpha, double beta, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) w[i] = w[i] - alpha * v[i] - beta * vp[i];
+}
+
+// Label assignment (Algorithm 3, last loop): dec_j = sum_i zy_i exp(-||f_i - g_j||^2 / (2h^2)) + b.
+// A workgroup owns 64 test points (tile in LDS) and walks over the training points 64 at a time; thread
+// (g, j) accumulates training points g, g+4, ... of each tile for test point j.
+__global__ __launch_bounds__(256) void decision_kernel(const double* __restrict__ Fp, const double* __restrict__ zy,
+                                                       int64_t n, const double* __restrict__ G, int64_t n_test, int r,
+                                                       int r_pad, double inv2h2, double bias, double* __restrict__ dec) {
+    extern __shared__ double sm[];
+    const int ldf = r_pad + 1;
+    double* Gs = sm;                  // 64 x ldf
+    double* Fs = sm + 64 * ldf;       // 64 x ldf
+    double* zs = Fs + 64 * ldf;       // 64
+    double* red = zs + 64;            // 4 x 64
+    const int tid = threadIdx.x;
+    const int j = tid & 63, g = tid >> 6;
+    const int64_t j0 = (int64_t)blockIdx.x * 64;
+    for (int idx = tid; idx < 64 * r_pad; idx += 256) {
+        int q = idx / r_pad, f = idx - q * r_pad;
+        Gs[q * ldf + f] = (j0 + q < n_test && f < r) ? G[(j0 + q) * r + f] : 0.0;
+    }
+    double acc = 0.0;
+    for (int64_t i0 = 0; i0 < n; i0 += 64) {
+        __syncthreads();
+        for (int idx = tid; idx < 64 * r_pad; idx += 256) {
+            int q = idx / r_pad, f = idx - q * r_pad;
+            Fs[q * ldf + f] = (i0 + q < n) ? Fp[(i0 + q) * r_pad + f] : 0.0;
+        }
+        if (tid < 64) zs[tid] = (i0 + tid < n) ? zy[i0 + tid] : 0.0;
+        __syncthreads();
+        for (int q = g; q < 64; q += 4) {
+            const double c = zs[q];
+            if (c == 0.0) continue;
+            double d2 = 0.0;
+            for (int f = 0; f < r_pad; ++f) {
+                double d = Fs[q * ldf + f] - Gs[j * ldf + f];
+                d2 += d * d;
+            }
+            acc += c * exp(-d2 * inv2h2);
+        }
+    }
+    red[g * 64 + j] = acc;
+    __syncthreads();
+    if (g == 0 && j0 + j < n_test) dec[j0 + j] = ((red[j] + red[64 + j]) + red[128 + j]) + red[192 + j] + bias;
+}
+
+}  // namespace
+
+static unsigned eb(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+int vec_blocks(int64_t n) {
+    int64_t b = (n + 255) / 256;
+    if (b > VEC_BLOCKS) b = VEC_BLOCKS;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+int vec_gather(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n) {
+    hipLaunchKernelGGL(gather_kernel, dim3(eb(n)), dim3(256), 0, st, dst, src, perm, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_scatter(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n) {
+    hipLaunchKernelGGL(scatter_kernel, dim3(eb(n)), dim3(256), 0, st, dst, src, perm, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_mul(hipStream_t st, double* dst, const double* a, const double* b, int64_t n) {
+    hipLaunchKernelGGL(mul_kernel, dim3(eb(n)), dim3(256), 0, st, dst, a, b, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+// *out_dev = sum a[i]*b[i] (b null: sum a[i]); partial_dev: at least VEC_BLOCKS doubles
+int vec_dot(hipStream_t st, const double* a, const double* b, int64_t n, double* partial_dev, double* out_dev) {
+    const int nb = vec_blocks(n);
+    hipLaunchKernelGGL(dot_partial_kernel, dim3(nb), dim3(256), 0, st, a, b, n, partial_dev);
+    hipLaunchKernelGGL(finish_sum_kernel, dim3(1), dim3(256), 0, st, partial_dev, nb, out_dev);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_axpby(hipStream_t st, double* y, const double* x, double a, double b, int64_t n) {
+    hipLaunchKernelGGL(axpby_kernel, dim3(eb(n)), dim3(256), 0, st, y, x, a, b, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, double alpha, double beta, int64_t n) {
+    hipLaunchKernelGGL(lanczos_update_kernel, dim3(eb(n)), dim3(256), 0, st, w, v, vp, alpha, beta, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, double* part_out) {
+    hipLaunchKernelGGL(admm_start_kernel, dim3(vec_blocks(n)), dim3(256), 0, st, v, n, part_out);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, double C, double beta, const double* w1_dev,
+              const double* part_in, double* part_out) {
+    const int nb = vec_blocks(n);
+    hipLaunchKernelGGL(admm_step_kernel, dim3(nb), dim3(256), 0, st, v, n, C, beta, w1_dev, part_in, nb, part_out);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int margin_indicator(hipStream_t st, const double* z, double C, double* ebar, int64_t n) {
+    hipLaunchKernelGGL(margin_kernel, dim3(eb(n)), dim3(256), 0, st, z, C, ebar, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+// out_dev[0] = sum_M y_j, out_dev[1] = sum_i y_i z_i u_i, out_dev[2] = |M|; partial_dev: 3*VEC_BLOCKS doubles
+int bias_sums(hipStream_t st, const double* z, const double* y, const double* u, const double* ebar, int64_t n,
+              double* partial_dev, double* out_dev) {
+    const int nb = vec_blocks(n);
+    hipLaunchKernelGGL(bias_partial_kernel, dim3(nb), dim3(256), 0, st, z, y, u, ebar, n, partial_dev);
+    hipLaunchKernelGGL(finish_sum3_kernel, dim3(1), dim3(256), 0, st, partial_dev, nb, out_dev);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int decision_launch(hipStream_t st, const double* Fp, const double* zy, int64_t n, const double* G, int64_t n_test, int r,
+                    int r_pad, double h, double bias, double* dec) {
+    if (n_test <= 0) return HSS_OK;
+    size_t smem = sizeof(double) * (128 * (r_pad + 1) + 64 + 256);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(decision_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem));
+    hipLaunchKernelGGL(decision_kernel, dim3((unsigned)((n_test + 63) / 64)), dim3(256), smem, st, Fp, zy, n, G, n_test, r,
+                       r_pad, 1.0 / (2.0 * h * h), bias, dec);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}

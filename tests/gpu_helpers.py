@@ -1,0 +1,48 @@
+"""Helpers shared by the GPU tests: access to the library's internal test entry points and the
+bridge from an exported compressed matrix to the oracle's HSS container."""
+import ctypes as C
+
+import numpy as np
+
+from oracle import hss as ohss
+from paper_2108_04167_amd import binding
+
+
+def lib():
+    return binding.load()
+
+
+def dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+def ptr(t):
+    return C.c_void_p(t.data_ptr())
+
+
+def hptr(a):
+    return C.c_void_p(a.ctypes.data)
+
+
+def oracle_hss_from_export(exp, with_shift=True):
+    """Oracle HSS container holding exactly the generators the library exported (plus the guard's
+    diagonal shift when with_shift)."""
+    n, leaf = int(exp["n"]), int(exp["leaf"])
+    H = ohss.HSS(n, leaf)
+    sizes, ranks = exp["sizes"], exp["ranks"]
+    uo = jo = bo = 0
+    for t in range(1, H.nnodes):
+        m, k = int(sizes[t]), int(ranks[t])
+        H.U[t] = exp["U"][uo:uo + m * k].reshape(m, k).copy()
+        H.J[t] = exp["J"][jo:jo + k].astype(np.int64)
+        uo += m * k
+        jo += k
+    for t in range(H.first_leaf()):
+        ka, kb = int(ranks[2 * t + 1]), int(ranks[2 * t + 2])
+        H.B[t] = exp["B"][bo:bo + ka * kb].reshape(ka, kb).copy()
+        bo += ka * kb
+    shift = exp["delta"] if with_shift else 0.0
+    H.D = [exp["D"][i] + shift * np.eye(leaf) for i in range(n // leaf)]
+    assert uo == exp["U"].size and bo == exp["B"].size
+    return H
