@@ -62,7 +62,9 @@ void hss_destroy(hss_ctx* ctx);
 
 /* Options; set before hss_compress.
  *   i64: "sample_width" s   number of random columns (default 128; padded with zero columns to a multiple of 128 inside)
- *        "oversample"   p   rank cap is s - p unless "max_rank" is set (default 10)   (oversampling, end of Sec. 3.2)
+ *        "oversample"   p   rank cap is s - p unless "max_rank" is set (default s/2: with ranks that hit the
+ *                           cap a small p over-fits the sample and the nested bases amplify the error
+ *                           level by level)                                    (oversampling, end of Sec. 3.2)
  *        "max_rank"         explicit rank cap per node (default 0 = s - p)
  *        "seed"             seed of the counter-based generator that draws Omega (default 0)
  *        "psd_guard"        1 (default): after compression estimate lambda_min(K~) and, if negative,
@@ -130,6 +132,7 @@ typedef struct hss_stats_t {
     double  delta;                     /* diagonal shift added by the definiteness guard                    */
     double  beta;                      /* factored beta, or -1                                              */
     double  t_tree, t_sample, t_levels, t_guard, t_factor;   /* seconds, last call of each phase            */
+    double  t_sample_kernel;           /* seconds of the K*Omega kernel alone (HIP events on the stream)      */
     int32_t warnings;                  /* OR of HSS_W* seen since the last compress                         */
     int32_t reserved;
 } hss_stats_t;

@@ -22,7 +22,7 @@ class HssStats(C.Structure):
                 ("generator_bytes", C.c_int64), ("factor_bytes", C.c_int64), ("factor_bytes_compact", C.c_int64),
                 ("sample_flops", C.c_double), ("delta", C.c_double), ("beta", C.c_double),
                 ("t_tree", C.c_double), ("t_sample", C.c_double), ("t_levels", C.c_double),
-                ("t_guard", C.c_double), ("t_factor", C.c_double),
+                ("t_guard", C.c_double), ("t_factor", C.c_double), ("t_sample_kernel", C.c_double),
                 ("warnings", C.c_int32), ("reserved", C.c_int32)]
 
 

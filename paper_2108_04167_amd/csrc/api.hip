@@ -210,6 +210,7 @@ int hss_stats(hss_ctx* c, hss_stats_t* o) {
     o->beta = c->factored ? c->beta : -1.0;
     o->t_tree = c->t_tree; o->t_sample = c->t_sample; o->t_levels = c->t_levels; o->t_guard = c->t_guard;
     o->t_factor = c->t_factor;
+    o->t_sample_kernel = c->t_sample_kernel;
     o->warnings = c->warnings;
     return HSS_OK;
 }

@@ -41,7 +41,7 @@ struct Level {
 struct hss_ctx {
     hipStream_t stream = nullptr;
     // options
-    int64_t opt_s = 128, opt_p = 10, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;
+    int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
     double  opt_abs_tol = 1e-8;
     // problem
     bool compressed = false, factored = false;
@@ -62,6 +62,7 @@ struct hss_ctx {
     DevBuf partial, scal;                   // reduction partials (4*VEC_BLOCKS), device scalars (16)
     // stats
     double sample_flops = 0.0, t_tree = 0.0, t_sample = 0.0, t_levels = 0.0, t_guard = 0.0, t_factor = 0.0;
+    double t_sample_kernel = 0.0;           // HIP-event time of the sampling kernel alone
     int64_t generator_bytes = 0, factor_bytes = 0, factor_bytes_compact = 0;
 };
 

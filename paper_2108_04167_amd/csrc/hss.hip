@@ -205,7 +205,8 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     if (s < 1) return HSS_EINVAL;
     const int s_pad = (int)round_up(s, 128);
     if (s_pad > 512) return HSS_EUNSUPPORTED;
-    int64_t kcap = c->opt_max_rank > 0 ? c->opt_max_rank : (int64_t)s - c->opt_p;
+    const int64_t p_over = c->opt_p >= 0 ? c->opt_p : (int64_t)s / 2;
+    int64_t kcap = c->opt_max_rank > 0 ? c->opt_max_rank : (int64_t)s - p_over;
     if (kcap > s) kcap = s;
     if (kcap < 1) return HSS_EINVAL;
     if (kcap > 512) return HSS_EUNSUPPORTED;
@@ -259,9 +260,21 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     t0 = wall();
     if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Om0.as<double>(), n, n_pad, s, s_pad));
     else HSS_TRY(omega_fill_launch(st, Om0.as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
-    HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Om0.as<double>(), S0.as<double>(), n_pad, r_pad,
-                          s_pad, h));
-    HIP_TRY(hipStreamSynchronize(st));
+    hipEvent_t ev0, ev1;
+    HIP_TRY(hipEventCreate(&ev0));
+    HIP_TRY(hipEventCreate(&ev1));
+    HIP_TRY(hipEventRecord(ev0, st));
+    int src = sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Om0.as<double>(), S0.as<double>(), n_pad, r_pad,
+                            s_pad, h);
+    (void)hipEventRecord(ev1, st);
+    hipError_t serr = hipStreamSynchronize(st);
+    float ms = 0.f;
+    if (src >= 0 && serr == hipSuccess) (void)hipEventElapsedTime(&ms, ev0, ev1);
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    if (src < 0) return src;
+    if (serr != hipSuccess) return HSS_EHIP;
+    c->t_sample_kernel = ms * 1e-3;
     c->t_sample = wall() - t0;
     c->sample_flops = 2.0 * (double)n * (double)n * (double)(s + r);
 

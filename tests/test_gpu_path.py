@@ -56,7 +56,8 @@ SMALL = {
     "cfg3_small": (3, 2048, 256, 512, {}),
     "cfg4_small": (4, 1024, 256, 512, {}),                      # a single level above the leaves
     "cfg5_small": (5, 2048, 256, 512, {}),
-    "lowrank_ragged": (1, 2048, 32, 128, {"h": 20.0, "tol": 1e-6}),   # tolerance-driven, ragged ranks, no saturation
+    "lowrank_ragged": (1, 2048, 32, 128, {"h": 20.0, "tol": 1e-6, "max_rank": 118}),   # tolerance-driven ragged ranks
+    "small_oversampling": (1, 1024, 64, 128, {"max_rank": 118}),   # rank cap s - 10: heavy saturation, large shift
     "one_leaf": (1, 64, 64, 128, {}),                           # L = 0: the HSS matrix is one dense block
     "two_leaves": (4, 64, 32, 128, {}),
 }
@@ -66,9 +67,11 @@ SMALL = {
 def case(request):
     cfg, n, leaf, s, over = SMALL[request.param]
     w = synth.make_workload(cfg, n=n, leaf=leaf, s=s)
+    over = dict(over)
+    max_rank = over.pop("max_rank", None)
     for k, v in over.items():
         setattr(w, k, v)
-    c = Case(w)
+    c = Case(w, max_rank=max_rank)
     c.name = request.param
     yield c
     c.close()
@@ -96,7 +99,7 @@ def test_p1_reconstruction_as_good_as_the_oracles(case):
     Ho = ohss.compress(Fp, w.h, w.leaf, case.Om[case.perm], w.tol / 10.0, 1e-8, st["rank_cap"])
     err_or = np.linalg.norm(K - ohss.densify(Ho)) / np.linalg.norm(K)
     ranks = case.exp["ranks"]
-    assert ranks[1:].min() >= 1 and ranks.max() <= st["rank_cap"]
+    assert ranks.max() <= st["rank_cap"] and (ranks.size == 1 or ranks[1:].min() >= 1)
     assert np.array_equal(Kt, Kt.T)
     # both are valid compressions of the same sample; neither may be markedly worse than the other
     assert err_gpu <= max(w.tol, 1.5 * err_or), (err_gpu, err_or)
@@ -190,7 +193,7 @@ def test_refactor_and_retrain_are_reproducible(case):
     assert case.ctx.hss_stats()["beta"] == 1.0
     for key in ("x", "z", "mu"):
         assert np.array_equal(a[key].cpu().numpy(), c[key].cpu().numpy())
-        assert not np.array_equal(a[key].cpu().numpy(), b[key].cpu().numpy())
+    assert not np.array_equal(a["x"].cpu().numpy(), b["x"].cpu().numpy())
     assert a["bias"] == c["bias"]
 
 
