@@ -1,0 +1,148 @@
+"""Benchmark of the shifted-kernel-solve hot path on one MI355X.
+
+A step is one pass of the whole path on one batch of synthetic input already resident in HBM:
+HSS compression (cluster tree, K*Omega sampling, interpolative decompositions, definiteness guard),
+ULV factorization of K~ + beta I, and the ADMM run (maxit iterations, one ULV solve each) with the
+bias.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP64_MFMA_PEAK_TFLOPS = 78.6
+
+
+def cpu_baseline(cfg, n_small, maxit):
+    """The oracle, as it stands, on a bounded cut of the same workload (host cores of this machine)."""
+    import numpy as np
+    from oracle import admm as oadmm
+    from oracle import hss as ohss
+    from oracle import ulv as oulv
+    from oracle.tree import cluster_tree
+    from paper_2108_04167_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    w = synth.make_workload(cfg, n=n_small)
+    t0 = time.time()
+    perm = cluster_tree(w.F, w.leaf)
+    Fp, yp = w.F[perm], w.y[perm]
+    Om = w.omega()[perm]
+    t1 = time.time()
+    S = ohss.sample(Fp, Om, w.h)
+    t2 = time.time()
+    H = ohss.compress(Fp, w.h, w.leaf, Om, w.tol / 10.0, 1e-8, w.s // 2, S=S)
+    ohss.add_diagonal(H, ohss.psd_shift(H))
+    Fz = oulv.ulv_factor(H, w.beta)
+    out = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), yp, w.C, w.beta, maxit)
+    oadmm.bias(out["z"], yp, w.C, lambda v: ohss.matvec(H, v))
+    t3 = time.time()
+    return {"n": n_small, "t_sampling": t2 - t1, "t_rest": (t1 - t0) + (t3 - t2), "threads": threads}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--cfg", type=int, default=3, help="workload 1..5 (default 3: n=262144, the metric's config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2108_04167_amd import binding, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.load()
+    dev = torch.device("cuda:0")
+    w = synth.make_workload(args.cfg)
+    F = torch.tensor(w.F, device=dev)
+    y = torch.tensor(w.y, device=dev)
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", w.s)
+
+    def step():
+        ctx.hss_compress(F, y, w.h, w.leaf, w.tol)                 # draws Omega in-library
+        st = ctx.hss_stats()
+        t0 = time.perf_counter()
+        out = ctx.admm_svm_train(w.C, w.beta, w.maxit)              # factors, iterates, computes the bias
+        torch.cuda.synchronize()
+        t_train = time.perf_counter() - t0
+        st2 = ctx.hss_stats()
+        return st, st2, t_train, out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    t_kernel = 0.0
+    t_solve_iter = 0.0
+    last = None
+    for _ in range(args.steps):
+        st, st2, t_train, out = step()
+        t_kernel += st["t_sample_kernel"]
+        t_solve_iter += max(t_train - st2["t_factor"], 0.0) / max(w.maxit, 1)
+        last = (st, st2, t_train, out)
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t_begin
+    per_step = total / args.steps
+    st, st2, t_train, out = last
+    t_kernel /= args.steps
+    t_solve_iter /= args.steps
+    n, r, s = w.n, w.r, w.s
+    flops = 2.0 * n * n * (s + r)
+    tf = flops / t_kernel / 1e12
+    solve_gbs = st2["factor_bytes"] / t_solve_iter / 1e9
+
+    # accuracy of the trained model (exact kernel), reported for context
+    dec = ctx.svm_decision(torch.tensor(w.F_test, device=dev), out["z"], out["bias"])
+    acc = float((((dec >= 0).double() * 2 - 1) == torch.tensor(w.y_test, device=dev)).double().mean().item() * 100)
+
+    rec = {
+        "metric": "admm_hss_train_seconds", "value": per_step, "unit": "s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"cfg{args.cfg}", "n": n, "r": r, "h": w.h, "C": w.C, "leaf": w.leaf, "tol": w.tol,
+                   "sample_width": s, "rank_cap": st["rank_cap"], "beta": w.beta, "admm_iterations": w.maxit},
+        "phases_s": {"tree": st["t_tree"], "sampling": st["t_sample"], "levels": st["t_levels"], "guard": st["t_guard"],
+                     "factor": st2["t_factor"], "admm_and_bias": t_train - st2["t_factor"]},
+        "roofline": {"kernel": "sample_kernel (S = K*Omega, fused Gram+exp+contraction)", "bound": "mfma",
+                     "achieved": tf, "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / FP64_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops, "seconds_per_launch": t_kernel},
+        "roofline_solve": {"kernel": "solve_gemv_kernel (ULV up/down sweeps, per ADMM iteration incl. vector update)",
+                           "bound": "hbm", "achieved": solve_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": solve_gbs / HBM_PEAK_GBS, "traffic": None,
+                           "bytes_per_solve": st2["factor_bytes"], "bytes_per_solve_compact": st2["factor_bytes_compact"],
+                           "seconds_per_iteration": t_solve_iter},
+        "model": {"delta": st["delta"], "rank_max": st["rank_max"], "nodes_at_cap": st["nodes_at_cap"],
+                  "bias": out["bias"], "n_margin": out["n_margin"], "test_accuracy_pct": acc, "warnings": st2["warnings"]},
+    }
+    if not args.no_cpu_baseline:
+        n_small = min(n, 4096 if args.cfg != 1 else 2048)
+        cb = cpu_baseline(args.cfg, n_small, w.maxit)
+        scale = n / cb["n"]
+        est = cb["t_sampling"] * scale * scale + cb["t_rest"] * scale
+        rec["cpu_baseline"] = {
+            "value": est, "unit": "s", "cores": cb["threads"], "kind": "oracle",
+            "sample": (f"whole oracle train (tree, K*Omega, HSS, guard, ULV, {w.maxit} ADMM iterations, bias) on the "
+                       f"cfg{args.cfg} generator cut to n={cb['n']}: sampling {cb['t_sampling']:.2f} s, rest "
+                       f"{cb['t_rest']:.2f} s; value extrapolates sampling by (n/n_cut)^2 and the rest by n/n_cut"),
+        }
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
