@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--cfg", type=int, default=3, help="workload 1..5 (default 3: n=262144, the metric's config)")
+    ap.add_argument("--n", type=int, default=0, help="cut the workload to n points (profiling runs only; 0 = full size)")
+    ap.add_argument("--copy-probe", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many bytes (reference for HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -68,7 +71,13 @@ def main():
         sys.exit(1)
     binding.load()
     dev = torch.device("cuda:0")
-    w = synth.make_workload(args.cfg)
+    w = synth.make_workload(args.cfg, n=args.n or None)
+    if args.copy_probe > 0:
+        src = torch.ones(args.copy_probe // 8, dtype=torch.float64, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     F = torch.tensor(w.F, device=dev)
     y = torch.tensor(w.y, device=dev)
     ctx = binding.Context()
@@ -115,7 +124,7 @@ def main():
         "metric": "admm_hss_train_seconds", "value": per_step, "unit": "s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-        "config": {"workload": f"cfg{args.cfg}", "n": n, "r": r, "h": w.h, "C": w.C, "leaf": w.leaf, "tol": w.tol,
+        "config": {"workload": f"cfg{args.cfg}" + (f" cut to n={n}" if args.n else ""), "n": n, "r": r, "h": w.h, "C": w.C, "leaf": w.leaf, "tol": w.tol,
                    "sample_width": s, "rank_cap": st["rank_cap"], "beta": w.beta, "admm_iterations": w.maxit},
         "phases_s": {"tree": st["t_tree"], "sampling": st["t_sample"], "levels": st["t_levels"], "guard": st["t_guard"],
                      "factor": st2["t_factor"], "admm_and_bias": t_train - st2["t_factor"]},

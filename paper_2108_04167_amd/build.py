@@ -40,6 +40,13 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
+    # stand-alone driver of the C ABI (for hardware-counter runs that must wrap a plain executable)
+    drv = os.path.join(HERE, "native", "hss_bench_native")
+    cmd = [hipcc, "-O2", "-std=c++17", os.path.join(HERE, "native", "hss_bench_native.cpp"), "-o", drv,
+           "-L" + HERE, "-lhsssvm", "-Wl,-rpath,$ORIGIN/.."]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"native driver failed:\n{res.stdout}\n{res.stderr}")
     return LIB
 
 

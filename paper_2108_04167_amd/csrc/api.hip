@@ -58,7 +58,7 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
     if (r > 96) return HSS_EUNSUPPORTED;
     hipStream_t st = ctx->stream;
     const int64_t n_pad = round_up(n, 256);
-    const int r_pad = (int)round_up(r, 4), s_pad = (int)round_up(s, 128);
+    const int r_pad = feature_pad(r), s_pad = (int)round_up(s, 128);
     DevBuf Fp, nu, Om, S;
     HSS_TRY(Fp.reserve(sizeof(double) * n_pad * r_pad));
     HSS_TRY(nu.reserve(sizeof(double) * n_pad));

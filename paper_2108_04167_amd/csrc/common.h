@@ -23,6 +23,9 @@
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+// Feature count after zero padding: the sampling kernel issues its Gram k-steps (4 features each) in
+// 7 equal groups per column block, so it wants a multiple of 28.
+static inline int feature_pad(int r) { return (int)round_up(r, 28); }
 
 // ---------------------------------------------------------------------------------------------
 // Device buffer with ownership.
@@ -116,7 +119,7 @@ int bgemm(hipStream_t st, const GemmItem* items_dev, int nitems, int maxM, int m
 // ---------------------------------------------------------------------------------------------
 // Sampling S = K(Fp,Fp) * Omega (fused Gram + exp + contraction on the matrix cores).
 // Fp: n_pad x r_pad (zero padded), nu: n_pad squared norms, Om/S: n_pad x s_pad, n_pad % 256 == 0,
-// r_pad % 4 == 0 (<= 96), s_pad % 128 == 0.
+// r_pad % 28 == 0 (<= 112), s_pad % 128 == 0.
 int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S,
                   int64_t n_pad, int r_pad, int s_pad, double h);
 int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad);

@@ -219,7 +219,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
     c->h = h; c->tol = tol; c->delta = 0.0; c->beta = -1.0; c->warnings = 0;
-    c->r_pad = (int)round_up(r, 4);
+    c->r_pad = feature_pad(r);
     c->n_pad = round_up(n, 256);
     const int r_pad = c->r_pad;
     const int64_t n_pad = c->n_pad;

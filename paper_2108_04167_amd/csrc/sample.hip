@@ -17,22 +17,60 @@
 namespace {
 
 constexpr int BN = 32;          // points per j-block
-constexpr int MAXF = 8;         // F_j tile elements staged per thread (32 * r_pad <= 8 * 512)
 
-template <int WR, int WC, int CT>
+// Constants of e^x on the vector ALUs, read through scalar loads so that they live in scalar registers
+// (literal operands would be re-materialised into vector registers inside the loop).
+//   [0] 64/ln2, [1] -(ln2/64) high part, [2] -(ln2/64) low part, [3..6] 1/120, 1/24, 1/6, 1/2
+__constant__ double EXPC[8] = {
+    92.332482616893656877, -1.08304246932675596327e-02, -2.98158582698529328128e-12,
+    1.0 / 120.0, 1.0 / 24.0, 1.0 / 6.0, 0.5, 0.0};
+
+// e^x for x <= 0 to within two ulp: x = (64 m + j) ln2/64 + r with |r| <= ln2/128,
+// e^x = 2^m * T[j] * (1 + r (1 + r/2 + r^2/6 + r^3/24 + r^4/120)), T[j] = 2^(j/64) from an LDS table
+// (remainder r^6/720 < 4e-17); underflows to 0 through the exponent scaling.
+// a * b + c with the addend held in scalar registers (the compiler would otherwise copy the constant
+// into vector registers to use the two-address form).
+__device__ __forceinline__ double fma_vvs(double a, double b, double c_uniform) {
+    double d;
+    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "s"(c_uniform));
+    return d;
+}
+
+__device__ __forceinline__ double exp_nonpos(double x, const double (&c)[8], const double* __restrict__ tab) {
+    const double kf = __builtin_rint(x * c[0]);
+    const int ki = (int)kf;
+    double r = __builtin_fma(kf, c[1], x);
+    r = __builtin_fma(kf, c[2], r);
+    const double T = tab[ki & 63];
+    double q = fma_vvs(r, c[7], c[4]);      // c[7] = 1/120 kept in a vector register by the caller
+    q = fma_vvs(q, r, c[5]);
+    q = fma_vvs(q, r, c[6]);
+    q = __builtin_fma(q, r, 1.0);
+    return __builtin_amdgcn_ldexp(__builtin_fma(T, q * r, T), ki >> 6);
+}
+
+// One workgroup of 8 wavefronts (WR x WC); every wavefront owns a 64 x (16*CT) block of S.
+// GP: Gram k-steps issued per contraction k-step; the feature dimension is padded to r_pad = 28 * GP.
+template <int WR, int WC, int CT, int GP>
 __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ Fp, const double* __restrict__ nu,
                                                       const double* __restrict__ Om, double* __restrict__ S,
-                                                      int n_pad, int r_pad, int s_pad, double inv2h2) {
+                                                      int n_pad, int s_pad, double inv2h2) {
     static_assert(WR * WC == 8, "8 wavefronts");
     constexpr int BMR = 64 * WR;           // rows of S per workgroup
-    constexpr int LDK = BMR + 16;          // leading dimension of the K tile (j-major)
+    constexpr int LDK = BMR + 1;           // leading dimension of the K tile (j-major); odd: the exp results of 16 lanes
+                                           // (consecutive j, stride LDK) then fall into 16 distinct bank pairs
+    constexpr int NK4 = 7 * GP;            // Gram k-steps
+    constexpr int RP = 4 * NK4;            // padded feature count
+    constexpr int LDF = RP + 1;
+    constexpr int TILE = BN * RP;          // doubles in one F_j tile (contiguous in Fp)
+    constexpr int MAXF = (TILE + 511) / 512;
     extern __shared__ double smem[];
-    const int ldf = r_pad + 1;
-    double* Fi_s = smem;                           // BMR x ldf
-    double* Fj_s = Fi_s + BMR * ldf;               // 2 x BN x ldf
-    double* nui_s = Fj_s + 2 * BN * ldf;           // BMR
-    double* nuj_s = nui_s + BMR;                   // 2 x BN
-    double* K_s = nuj_s + 2 * BN;                  // 2 x BN x LDK
+    double* Fi_s = smem;                           // BMR x LDF
+    double* Fj_s = Fi_s + BMR * LDF;               // 2 x BN x LDF
+    double* nui_s = Fj_s + 2 * BN * LDF;           // BMR        holds -nu_i / (2h^2)
+    double* nuj_s = nui_s + BMR;                   // 2 x BN     holds -nu_j / (2h^2)
+    double* tab_s = nuj_s + 2 * BN;                // 64         2^(j/64)
+    double* K_s = tab_s + 64;                      // 2 x BN x LDK
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -41,47 +79,57 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
     const int row0 = blockIdx.x * BMR;
     const int col0 = (blockIdx.y * WC + wc) * (16 * CT);
     const int NJ = n_pad / BN;
-    const int tile_elems = BN * r_pad;
+    const double invh2 = 2.0 * inv2h2;
 
-    // ---- prologue: F_i tile, nu_i, F_j tiles 0 and 1 ----
-    for (int idx = tid; idx < BMR * r_pad; idx += 512) {
-        int rr = idx / r_pad, cc = idx - rr * r_pad;
-        Fi_s[rr * ldf + cc] = Fp[(size_t)row0 * r_pad + idx];
+    double ec[8];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) ec[i] = EXPC[i];
+    {   // 1/120 as a vector-register operand (an instruction reads at most one scalar-register constant)
+        double c3v;
+        asm volatile("v_mov_b64 %0, %1" : "=v"(c3v) : "s"(EXPC[3]));
+        ec[7] = c3v;
     }
-    for (int idx = tid; idx < BMR; idx += 512) nui_s[idx] = nu[row0 + idx];
+
+    // ---- prologue: exp table, F_i tile, nu_i, F_j tiles 0 and 1 ----
+    if (tid < 64) tab_s[tid] = exp2((double)tid * (1.0 / 64.0));
+    for (int idx = tid; idx < BMR * RP; idx += 512) {
+        int rr = idx / RP, cc = idx - rr * RP;
+        Fi_s[rr * LDF + cc] = Fp[(size_t)row0 * RP + idx];
+    }
+    for (int idx = tid; idx < BMR; idx += 512) nui_s[idx] = -nu[row0 + idx] * inv2h2;
     for (int b = 0; b < 2; ++b) {
         int jb = b < NJ ? b : NJ - 1;
-        for (int idx = tid; idx < tile_elems; idx += 512) {
-            int rr = idx / r_pad, cc = idx - rr * r_pad;
-            Fj_s[(b * BN + rr) * ldf + cc] = Fp[(size_t)jb * tile_elems + idx];
+        for (int idx = tid; idx < TILE; idx += 512) {
+            int rr = idx / RP, cc = idx - rr * RP;
+            Fj_s[(b * BN + rr) * LDF + cc] = Fp[(size_t)jb * TILE + idx];
         }
-        if (tid < BN) nuj_s[b * BN + tid] = nu[jb * BN + tid];
+        if (tid < BN) nuj_s[b * BN + tid] = -nu[jb * BN + tid] * inv2h2;
     }
     __syncthreads();
 
-    // Gram + exp of one K tile (block jb, LDS buffer buf).  The tile has (4*WR) x 2 MFMA tiles;
-    // wavefront w computes tiles w*WR .. w*WR+WR-1.
-    auto make_ktile = [&](int buf) {
-        const double* Fj = Fj_s + buf * BN * ldf;
-        const double* nj = nuj_s + buf * BN;
-        double* Kt = K_s + buf * BN * LDK;
+    // The K tile of a column block has (4*WR) x 2 MFMA tiles; wavefront w computes tiles w*WR .. w*WR+WR-1:
+    // Gram accumulators g[u] (register v of lane (lk, lr) is G[4*v + lk][lr]), then
+    // K = exp(min(0, G/h^2 - nu_i/(2h^2) - nu_j/(2h^2))) written j-major into LDS.
+    auto gram_steps = [&](v4d (&g)[WR], const double* Fj, int q0, int q1) {   // k-steps q0 .. q1-1 (static)
 #pragma unroll
         for (int u = 0; u < WR; ++u) {
-            int t = wave * WR + u;
-            int rt = t >> 1, ct = t & 1;
-            v4d g = (v4d){0.0, 0.0, 0.0, 0.0};
-            const double* ap = Fi_s + (rt * 16 + lr) * ldf + lk;
-            const double* bp = Fj + (ct * 16 + lr) * ldf + lk;
-            for (int ks = 0; ks < r_pad; ks += 4) g = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[ks], bp[ks], g, 0, 0, 0);
-            double nuj = nj[ct * 16 + lr];
-            // accumulator register v of lane (lk, lr) is G[4*v + lk][lr]
-            double* kp = Kt + (ct * 16 + lr) * LDK + rt * 16 + lk;
+            const int t = wave * WR + u;
+            const double* ap = Fi_s + ((t >> 1) * 16 + lr) * LDF + lk;
+            const double* bp = Fj + ((t & 1) * 16 + lr) * LDF + lk;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                double d2 = nui_s[rt * 16 + 4 * v + lk] + nuj - 2.0 * g[v];
-                d2 = d2 > 0.0 ? d2 : 0.0;
-                kp[4 * v] = exp(-d2 * inv2h2);
-            }
+            for (int q = q0; q < q1; ++q) g[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(ap[4 * q], bp[4 * q], g[u], 0, 0, 0);
+        }
+    };
+    auto exp_store = [&](const v4d (&g)[WR], int buf, int v) {   // accumulator register v of every tile
+#pragma unroll
+        for (int u = 0; u < WR; ++u) {
+            const int t = wave * WR + u;
+            const int rt = t >> 1, ct2 = t & 1;
+            const double nj = nuj_s[buf * BN + ct2 * 16 + lr];
+            double* kp = K_s + buf * BN * LDK + (ct2 * 16 + lr) * LDK + rt * 16 + lk;
+            // (rounding can leave x a few ulp above 0 on the diagonal; e^x is then 1 to rounding)
+            const double x = __builtin_fma(g[u][v], invh2, nui_s[rt * 16 + 4 * v + lk] + nj);
+            kp[4 * v] = exp_nonpos(x, ec, tab_s);
         }
     };
 
@@ -91,27 +139,33 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
 #pragma unroll
         for (int j = 0; j < CT; ++j) acc[i][j] = (v4d){0.0, 0.0, 0.0, 0.0};
 
-    // Omega register ring, four k-steps deep: slot ks%4 holds Omega[jb*32 + ks*4 + lk][col0 + CT*lr + ct];
-    // a slot is refilled for the k-step four ahead right after it has been consumed.
-    double om[4][CT];
-    auto load_omega = [&](const double* op, int kstep, int ks) {
-        const double* q = op + (size_t)kstep * 4 * s_pad;
+    // Omega register ring, RING k-steps deep: slot ks%RING holds Omega[jb*32 + ks*4 + lk][col0 + CT*lr + ct];
+    // a slot is refilled for the k-step RING ahead right after it has been consumed.
+    constexpr int RING = (CT == 4) ? 2 : 4;
+    double om[RING][CT];
+    const size_t step_elems = (size_t)4 * s_pad;
+    auto load_omega = [&](const double* q, int slot) {
         if constexpr (CT == 4) {
             double2 q0 = reinterpret_cast<const double2*>(q)[0], q1 = reinterpret_cast<const double2*>(q)[1];
-            om[ks][0] = q0.x; om[ks][1] = q0.y; om[ks][2] = q1.x; om[ks][3] = q1.y;
+            om[slot][0] = q0.x; om[slot][1] = q0.y; om[slot][2] = q1.x; om[slot][3] = q1.y;
         } else if constexpr (CT == 2) {
             double2 q0 = reinterpret_cast<const double2*>(q)[0];
-            om[ks][0] = q0.x; om[ks][1] = q0.y;
+            om[slot][0] = q0.x; om[slot][1] = q0.y;
         } else {
-            om[ks][0] = q[0];
+            om[slot][0] = q[0];
         }
     };
-    {
-        const double* op = Om + (size_t)lk * s_pad + col0 + CT * lr;
+    const double* op = Om + (size_t)lk * s_pad + col0 + CT * lr;   // this lane's element of k-step 0 of block 0
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) load_omega(op, ks, ks);
+    for (int ks = 0; ks < RING; ++ks) load_omega(op + ks * step_elems, ks);
+    {
+        v4d g0[WR];
+#pragma unroll
+        for (int u = 0; u < WR; ++u) g0[u] = (v4d){0.0, 0.0, 0.0, 0.0};
+        gram_steps(g0, Fj_s, 0, NK4);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) exp_store(g0, 0, v);
     }
-    make_ktile(0);
     __syncthreads();
 
     double fj[MAXF];
@@ -120,43 +174,55 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
         const int cur = jb & 1, nxt = cur ^ 1;
         // stage F_j tile jb+2 in registers (stored to LDS at the end of this iteration)
         const int jb2 = jb + 2 < NJ ? jb + 2 : NJ - 1;
+        const double* fsrc = Fp + (size_t)jb2 * TILE + tid;
 #pragma unroll
-        for (int u = 0; u < MAXF; ++u) {
-            int idx = tid + u * 512;
-            fj[u] = idx < tile_elems ? Fp[(size_t)jb2 * tile_elems + idx] : 0.0;
-        }
-        if (tid < BN) nuj_next = nu[jb2 * BN + tid];
+        for (int u = 0; u < MAXF; ++u)
+            if ((u + 1) * 512 <= TILE || tid + u * 512 < TILE) fj[u] = fsrc[u * 512];
+        if (tid < BN) nuj_next = -nu[jb2 * BN + tid] * inv2h2;
 
-        if (jb + 1 < NJ) make_ktile(nxt);
-
-        // contraction with K tile jb
-        const double* Kt = K_s + cur * BN * LDK + wr * 64 + lr;
-        const int jbn = jb + 1 < NJ ? jb + 1 : jb;
-        const double* op_cur = Om + ((size_t)jb * BN + lk) * s_pad + col0 + CT * lr;
-        const double* op_nxt = Om + ((size_t)jbn * BN + lk) * s_pad + col0 + CT * lr;
+        // Contraction with K tile jb, software pipelined: the K-tile operands of k-step ks+1 are fetched from
+        // LDS before the MFMAs of step ks are issued.  The Gram tile of K tile jb+1 is spread over k-steps
+        // 0-3 and its exponentials over steps 4-7 (one accumulator register each), so vector-ALU work and
+        // Gram MFMAs sit between the contraction MFMAs instead of forming a workgroup-wide phase after the
+        // barrier.  (After the last column block the extra tile is computed from the clamped F_j tile and
+        // never used.)
+        const double* Kt = K_s + cur * BN * LDK + wr * 64 + lr + lk * LDK;
+        const double* Fjn = Fj_s + nxt * BN * LDF;
+        // Omega: block jb+1 is clamped to the last block (loads past it are never consumed)
+        const size_t wrap = (jb + 1 < NJ) ? 0 : (size_t)BN * s_pad;
+        v4d g[WR];
+#pragma unroll
+        for (int u = 0; u < WR; ++u) g[u] = (v4d){0.0, 0.0, 0.0, 0.0};
+        double an[4] = {Kt[0], Kt[16], Kt[32], Kt[48]};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const double* kp = Kt + (ks * 4 + lk) * LDK;
-            double a0 = kp[0], a1 = kp[16], a2 = kp[32], a3 = kp[48];
+            const double a0 = an[0], a1 = an[1], a2 = an[2], a3 = an[3];
+            if (ks < 7) {
+                const double* kp = Kt + (ks + 1) * 4 * LDK;
+                an[0] = kp[0]; an[1] = kp[16]; an[2] = kp[32]; an[3] = kp[48];
+            }
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                double b = om[ks & 3][ct];
+                double b = om[ks % RING][ct];
                 acc[0][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b, acc[0][ct], 0, 0, 0);
                 acc[1][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b, acc[1][ct], 0, 0, 0);
                 acc[2][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a2, b, acc[2][ct], 0, 0, 0);
                 acc[3][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a3, b, acc[3][ct], 0, 0, 0);
             }
-            if (ks < 4) load_omega(op_cur, ks + 4, ks);
-            else load_omega(op_nxt, ks - 4, ks - 4);
+            if (ks + RING < 8) load_omega(op + (ks + RING) * step_elems, ks % RING);
+            else load_omega(op + (ks + RING) * step_elems - wrap, ks % RING);
+            if (ks < 4) gram_steps(g, Fjn, (NK4 * ks) / 4, (NK4 * (ks + 1)) / 4);
+            else exp_store(g, nxt, ks - 4);
         }
+        op += (size_t)BN * s_pad;
 
         // publish F_j tile jb+2 into the buffer tile jb used
 #pragma unroll
         for (int u = 0; u < MAXF; ++u) {
-            int idx = tid + u * 512;
-            if (idx < tile_elems) {
-                int rr = idx / r_pad, cc = idx - rr * r_pad;
-                Fj_s[(cur * BN + rr) * ldf + cc] = fj[u];
+            const int idx = tid + u * 512;
+            if ((u + 1) * 512 <= TILE || idx < TILE) {
+                const int rr = idx / RP, cc = idx - rr * RP;
+                Fj_s[(cur * BN + rr) * LDF + cc] = fj[u];
             }
         }
         if (tid < BN) nuj_s[cur * BN + tid] = nuj_next;
@@ -179,20 +245,32 @@ template <int WR>
 size_t sample_smem(int r_pad) {
     int ldf = r_pad + 1;
     int bmr = 64 * WR;
-    return sizeof(double) * ((size_t)bmr * ldf + 2 * BN * ldf + bmr + 2 * BN + 2 * BN * (bmr + 16));
+    return sizeof(double) * ((size_t)bmr * ldf + 2 * BN * ldf + bmr + 2 * BN + 64 + 2 * BN * (bmr + 1));
+}
+
+template <int WR, int WC, int CT, int GP>
+int sample_go_g(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
+                int s_pad, double inv2h2) {
+    size_t smem = sample_smem<WR>(28 * GP);
+    auto kern = sample_kernel<WR, WC, CT, GP>;
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem));
+    dim3 grid((unsigned)(n_pad / (64 * WR)), (unsigned)(s_pad / (16 * CT * WC)));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, Fp, nu, Om, S, (int)n_pad, s_pad, inv2h2);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
 }
 
 template <int WR, int WC, int CT>
 int sample_go(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
               int r_pad, int s_pad, double inv2h2) {
-    size_t smem = sample_smem<WR>(r_pad);
-    auto kern = sample_kernel<WR, WC, CT>;
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem));
-    dim3 grid((unsigned)(n_pad / (64 * WR)), (unsigned)(s_pad / (16 * CT * WC)));
-    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, Fp, nu, Om, S, (int)n_pad, r_pad, s_pad, inv2h2);
-    HIP_TRY(hipGetLastError());
-    return HSS_OK;
+    switch (r_pad / 28) {
+        case 1: return sample_go_g<WR, WC, CT, 1>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 2: return sample_go_g<WR, WC, CT, 2>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 3: return sample_go_g<WR, WC, CT, 3>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 4: return sample_go_g<WR, WC, CT, 4>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        default: return HSS_EUNSUPPORTED;
+    }
 }
 
 __global__ void row_norms_kernel(const double* __restrict__ Fp, double* __restrict__ nu, int64_t n_pad, int r_pad) {
@@ -270,7 +348,7 @@ __global__ void omega_fill_kernel(double* __restrict__ Om, int64_t n, int64_t n_
 
 int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
                   int r_pad, int s_pad, double h) {
-    if (n_pad % 256 || r_pad % 4 || r_pad < 4 || r_pad > 96 || s_pad % 128 || s_pad < 128) return HSS_EUNSUPPORTED;
+    if (n_pad % 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 || s_pad % 128 || s_pad < 128) return HSS_EUNSUPPORTED;
     const double inv2h2 = 1.0 / (2.0 * h * h);
     // Widest block of S per workgroup whose column span divides s_pad and whose LDS footprint fits:
     // 64 x 512, else 128 x 256 (64 x 256 when the feature tiles are too large), else 128 x 128 (64 x 128).

@@ -1,0 +1,93 @@
+// Stand-alone driver of the C ABI (no Python): runs compress, factor, a few solves and a short ADMM run
+// on seeded synthetic points.  It exists so that hardware-counter collection (rocprofv3 --pmc) can wrap
+// a plain executable; the measured kernels and launch shapes are those of the library.
+//
+//   hss_bench_native n r s leaf h maxit [nsolve]
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "../../include/hss_svm.h"
+
+static uint64_t splitmix(uint64_t& s) {
+    s += 0x9E3779B97F4A7C15ull;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+static double uni(uint64_t& s) { return ((double)(splitmix(s) >> 11) + 0.5) / 9007199254740992.0; }
+static double now() {
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+#define CHECK(x)                                                              \
+    do {                                                                      \
+        int rc_ = (x);                                                        \
+        if (rc_ < 0) {                                                        \
+            fprintf(stderr, "%s failed: %s (%d)\n", #x, hss_strerror(rc_), rc_); \
+            return 1;                                                         \
+        }                                                                     \
+    } while (0)
+
+int main(int argc, char** argv) {
+    if (argc < 7) {
+        fprintf(stderr, "usage: %s n r s leaf h maxit [nsolve]\n", argv[0]);
+        return 2;
+    }
+    const int64_t n = atoll(argv[1]);
+    const int r = atoi(argv[2]), s = atoi(argv[3]), leaf = atoi(argv[4]);
+    const double h = atof(argv[5]);
+    const int maxit = atoi(argv[6]);
+    const int nsolve = argc > 7 ? atoi(argv[7]) : 5;
+    std::vector<double> F((size_t)n * r), y(n);
+    uint64_t sd = 2108;
+    for (int64_t i = 0; i < n; ++i) {
+        for (int f = 0; f < r; ++f) {
+            double u1 = uni(sd), u2 = uni(sd);
+            F[(size_t)i * r + f] = std::sqrt(-2.0 * std::log(u1)) * std::cos(6.283185307179586 * u2);
+        }
+        double sc = F[(size_t)i * r] + (r > 2 ? F[(size_t)i * r + 1] * F[(size_t)i * r + 2] : 0.0);
+        y[i] = sc >= 0.0 ? 1.0 : -1.0;
+    }
+    double *dF, *dy, *dx;
+    if (hipMalloc(&dF, sizeof(double) * n * r) != hipSuccess || hipMalloc(&dy, sizeof(double) * n) != hipSuccess ||
+        hipMalloc(&dx, sizeof(double) * n) != hipSuccess)
+        return 1;
+    hipMemcpy(dF, F.data(), sizeof(double) * n * r, hipMemcpyHostToDevice);
+    hipMemcpy(dy, y.data(), sizeof(double) * n, hipMemcpyHostToDevice);
+    hipMemcpy(dx, y.data(), sizeof(double) * n, hipMemcpyHostToDevice);
+    hss_ctx* ctx = nullptr;
+    CHECK(hss_create(&ctx, nullptr));
+    CHECK(hss_set_i64(ctx, "sample_width", s));
+    double t0 = now();
+    CHECK(hss_compress(ctx, dF, dy, n, r, h, leaf, 1e-3));
+    hipDeviceSynchronize();
+    double t1 = now();
+    CHECK(hss_ulv_factor(ctx, 1.0));
+    hipDeviceSynchronize();
+    double t2 = now();
+    for (int i = 0; i < nsolve; ++i) CHECK(hss_ulv_solve(ctx, dx, 1));
+    hipDeviceSynchronize();
+    double t3 = now();
+    double bias = 0.0;
+    int64_t nm = 0;
+    CHECK(admm_svm_train(ctx, 1.0, 1.0, maxit, nullptr, nullptr, nullptr, &bias, &nm));
+    double t4 = now();
+    hss_stats_t st;
+    CHECK(hss_stats(ctx, &st));
+    printf("n %lld r %d s %d leaf %d: compress %.4f s (sampling kernel %.4f s, %.2f TFLOP/s), factor %.4f s, "
+           "solve %.3f ms (%.1f GB/s), admm %d it %.4f s, bias %.6g, margin %lld, delta %.4g\n",
+           (long long)n, r, s, leaf, t1 - t0, st.t_sample_kernel, st.sample_flops / st.t_sample_kernel / 1e12, t2 - t1,
+           (t3 - t2) / nsolve * 1e3, st.factor_bytes / ((t3 - t2) / nsolve) / 1e9, maxit, t4 - t3, bias, (long long)nm,
+           st.delta);
+    hss_destroy(ctx);
+    hipFree(dF);
+    hipFree(dy);
+    hipFree(dx);
+    return 0;
+}
