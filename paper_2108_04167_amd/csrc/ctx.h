@@ -32,6 +32,10 @@ struct Level {
     DevBuf bvec, ce, xvec;                  // level vectors: input (sum msz), eliminated part (sum msz-rk), output (sum msz)
     DevBuf up_items, down_items, work;      // SolveItem tables and the (node, row block) work list
     int nwork = 0;
+    int rows_per_wave = 4;                  // launch shape of the level's solve kernel
+    bool vec = false;                       // 16-byte loads allowed (all sizes even)
+    bool skip = false;                      // leaf level where no node eliminates anything: the level above reads
+                                            // and writes the leaf vectors directly and no kernel is launched
     // mat-vec plumbing
     DevBuf xt, g;                           // (sum rk) each
     DevBuf mv_up, mv_dn_u, mv_dn_b, mv_dn_bt, mv_leaf_d;   // GemvItem tables

@@ -2,7 +2,6 @@
 #pragma once
 #include "common.h"
 
-constexpr int SOLVE_ROWS_PER_BLOCK = 32;
 
 struct SolveItem {           // y = M [in0(0:n0); in1(0:m-n0)];  y(0:nout0) -> out0, y(nout0:m) -> out1
     const double* M;         // m x m row-major (ld); null = identity (nothing eliminated at this node)
@@ -20,6 +19,8 @@ struct GemvItem {
     int32_t M, N, lda, pad;
 };
 
-int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork);
+// rows_per_wave in {1, 2, 4, 8}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node
+int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
+                       bool vec);
 int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool trans, double alpha,
                  double beta);

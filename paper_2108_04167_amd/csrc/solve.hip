@@ -7,12 +7,14 @@
 //   root             :  x = Dinv b
 //   down-sweep  node t:  x_t = Mdown_t [x_r; c_e]         (x_r handed down by the parent)
 // with dense m_t x m_t operators built at factorization time.  A launch processes one level; a work
-// list maps workgroups to (node, block of 32 rows) so that ragged node sizes need no padding.
+// list maps workgroups to (node, block of rows) so that ragged node sizes need no padding.
 #include "common.h"
 #include "solve.h"
 #include <algorithm>
 
 namespace {
+
+typedef double v2d __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -20,51 +22,73 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-constexpr int RB = SOLVE_ROWS_PER_BLOCK;   // 32 rows per workgroup, 8 per wavefront
-
+// One wavefront computes R consecutive rows of y = M x for one node; the input vector lives in registers
+// (lane l holds the columns it multiplies), so a wavefront issues its loads of x and of its R matrix rows
+// back to back and waits once.  VEC: 16-byte loads (needs even m, n0, ld and 16-byte aligned pointers).
+// A workgroup = 4 wavefronts = 4R rows; the work list gives (node, first row).
+template <int R, bool VEC>
 __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __restrict__ items,
                                                          const int2* __restrict__ work) {
     const int2 w = work[blockIdx.x];
     const SolveItem it = items[w.x];
-    const int row0 = w.y;
     const int m = it.m;
-    __shared__ double xs[1024];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (it.M == nullptr) {   // nothing was eliminated at this node: hand the vector through
-        for (int r = row0 + tid; r < row0 + RB && r < m; r += 256) {
+        for (int r = w.y + tid; r < w.y + 4 * R && r < m; r += 256) {
             double v = r < it.n0 ? it.in0[r] : it.in1[r - it.n0];
             if (r < it.nout0) it.out0[r] = v;
             else it.out1[r - it.nout0] = v;
         }
         return;
     }
-    for (int c = tid; c < m; c += 256) xs[c] = c < it.n0 ? it.in0[c] : it.in1[c - it.n0];
-    __syncthreads();
-    const int rbase = row0 + wave * 8;
+    const int row0 = w.y + wave * R;
+    if (row0 >= m) return;
+    constexpr int KMAX = 16;   // m <= 1024
+    double s[R];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int r = rbase + half * 4;
-        if (r >= m) break;
-        const double* a0 = it.M + (size_t)r * it.ld;
-        // rows past the end alias the last valid row (their sums are discarded)
-        const double* a1 = it.M + (size_t)(r + 1 < m ? r + 1 : m - 1) * it.ld;
-        const double* a2 = it.M + (size_t)(r + 2 < m ? r + 2 : m - 1) * it.ld;
-        const double* a3 = it.M + (size_t)(r + 3 < m ? r + 3 : m - 1) * it.ld;
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        for (int c = lane; c < m; c += 64) {
-            const double xv = xs[c];
-            s0 += a0[c] * xv;
-            s1 += a1[c] * xv;
-            s2 += a2[c] * xv;
-            s3 += a3[c] * xv;
+    for (int rr = 0; rr < R; ++rr) s[rr] = 0.0;
+    const double* rowp[R];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) rowp[rr] = it.M + (size_t)(row0 + rr < m ? row0 + rr : m - 1) * it.ld;
+    if (VEC) {
+#pragma unroll
+        for (int k = 0; k < KMAX / 2; ++k) {
+            const int c = 2 * lane + 128 * k;
+            if (128 * k < m) {          // uniform
+                double2 xv = make_double2(0.0, 0.0);
+                if (c < m) xv = c < it.n0 ? *reinterpret_cast<const double2*>(it.in0 + c)
+                                          : *reinterpret_cast<const double2*>(it.in1 + (c - it.n0));
+                const int cc = c < m ? c : 0;
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) {
+                    // streamed once per sweep: non-temporal, so the factors do not displace the vectors in cache
+                    const v2d a = __builtin_nontemporal_load(reinterpret_cast<const v2d*>(rowp[rr] + cc));
+                    s[rr] += a.x * xv.x + a.y * xv.y;
+                }
+            }
         }
-        s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2); s3 = wave_sum(s3);
-        if (lane < 4) {
-            const int rr = r + lane;
-            const double v = lane == 0 ? s0 : lane == 1 ? s1 : lane == 2 ? s2 : s3;
-            if (rr < m) {
-                if (rr < it.nout0) it.out0[rr] = v;
-                else it.out1[rr - it.nout0] = v;
+    } else {
+#pragma unroll
+        for (int k = 0; k < KMAX; ++k) {
+            const int c = lane + 64 * k;
+            if (64 * k < m) {           // uniform
+                double xv = 0.0;
+                if (c < m) xv = c < it.n0 ? it.in0[c] : it.in1[c - it.n0];
+                const int cc = c < m ? c : 0;
+#pragma unroll
+                for (int rr = 0; rr < R; ++rr) s[rr] += __builtin_nontemporal_load(rowp[rr] + cc) * xv;
+            }
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) s[rr] = wave_sum(s[rr]);
+    if (lane == 0) {
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+            const int r = row0 + rr;
+            if (r < m) {
+                if (r < it.nout0) it.out0[r] = s[rr];
+                else it.out1[r - it.nout0] = s[rr];
             }
         }
     }
@@ -118,9 +142,23 @@ __global__ __launch_bounds__(256) void bgemv_t_kernel(const GemvItem* __restrict
 
 }  // namespace
 
-int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork) {
+int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
+                       bool vec) {
     if (nwork <= 0) return HSS_OK;
-    hipLaunchKernelGGL(solve_gemv_kernel, dim3((unsigned)nwork), dim3(256), 0, st, items_dev, work_dev);
+    dim3 g((unsigned)nwork), b(256);
+#define HSS_SOLVE_CASE(R)                                                                                     \
+    case R:                                                                                                   \
+        if (vec) hipLaunchKernelGGL((solve_gemv_kernel<R, true>), g, b, 0, st, items_dev, work_dev);          \
+        else hipLaunchKernelGGL((solve_gemv_kernel<R, false>), g, b, 0, st, items_dev, work_dev);             \
+        break;
+    switch (rows_per_wave) {
+        HSS_SOLVE_CASE(1)
+        HSS_SOLVE_CASE(2)
+        HSS_SOLVE_CASE(4)
+        HSS_SOLVE_CASE(8)
+        default: return HSS_EINVAL;
+    }
+#undef HSS_SOLVE_CASE
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }

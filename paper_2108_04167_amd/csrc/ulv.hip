@@ -64,27 +64,45 @@ int build_solve_tables(hss_ctx* c) {
         HSS_TRY(lv.xvec.reserve(sizeof(double) * rows));
         HSS_TRY(lv.ce.reserve(sizeof(double) * std::max<int64_t>(rows - lv.koff[lv.N], 1)));
     }
+    // When no leaf eliminates anything (rank == leaf size everywhere) the leaves' vectors ARE the vectors of
+    // the level above (same layout), so that level works on them in place and the leaf level launches nothing.
+    bool leaves_pass = L >= 1;
+    for (int t = 0; leaves_pass && t < c->lev[L].N; ++t) leaves_pass = c->lev[L].pass[t] != 0;
+    for (int l = 0; l <= L; ++l) c->lev[l].skip = false;
+    if (leaves_pass) c->lev[L].skip = true;
     for (int l = L; l >= 0; --l) {
         Level& lv = c->lev[l];
         std::vector<SolveItem> up(lv.N), dn(lv.N);
+        double* my_bvec = (leaves_pass && l == L - 1) ? c->lev[L].bvec.as<double>() : lv.bvec.as<double>();
+        double* my_xvec = (leaves_pass && l == L - 1) ? c->lev[L].xvec.as<double>() : lv.xvec.as<double>();
         std::vector<int2> work;
+        // launch shape: enough workgroups to fill the chip (4 x rows_per_wave rows each); 16-byte loads when
+        // every size and offset of the level is even
+        int64_t rows_total = 0;
+        bool even = true;
+        for (int t = 0; t < lv.N; ++t) {
+            rows_total += lv.msz[t];
+            if ((lv.msz[t] | lv.rk[t]) & 1) even = false;
+        }
+        int rpw = 8;
+        while (rpw > 1 && rows_total / (4 * rpw) < 4096) rpw >>= 1;
+        lv.rows_per_wave = rpw;
+        lv.vec = even;
+        const int rb = 4 * rpw;
         for (int t = 0; t < lv.N; ++t) {
             const int m = lv.msz[t], k = lv.rk[t];
             if (l == 0) {
-                up[t] = SolveItem{c->rootinv.as<double>(), lv.bvec.as<double>(), nullptr, lv.xvec.as<double>(), nullptr,
-                                  m, m, m, m};
+                up[t] = SolveItem{c->rootinv.as<double>(), my_bvec, nullptr, my_xvec, nullptr, m, m, m, m};
                 dn[t] = up[t];
             } else {
                 Level& pl = c->lev[l - 1];
                 const double* Mu = lv.pass[t] ? nullptr : lv.Mup.as<double>() + lv.foff[t];
                 const double* Md = lv.pass[t] ? nullptr : lv.Mdown.as<double>() + lv.foff[t];
                 double* ce = lv.ce.as<double>() + (lv.moff[t] - lv.koff[t]);
-                up[t] = SolveItem{Mu, lv.bvec.as<double>() + lv.moff[t], nullptr, pl.bvec.as<double>() + lv.koff[t], ce,
-                                  m, m, m, k};
-                dn[t] = SolveItem{Md, pl.xvec.as<double>() + lv.koff[t], ce, lv.xvec.as<double>() + lv.moff[t], nullptr,
-                                  m, m, k, m};
+                up[t] = SolveItem{Mu, my_bvec + lv.moff[t], nullptr, pl.bvec.as<double>() + lv.koff[t], ce, m, m, m, k};
+                dn[t] = SolveItem{Md, pl.xvec.as<double>() + lv.koff[t], ce, my_xvec + lv.moff[t], nullptr, m, m, k, m};
             }
-            for (int r0 = 0; r0 < m; r0 += SOLVE_ROWS_PER_BLOCK) work.push_back(make_int2(t, r0));
+            for (int r0 = 0; r0 < m; r0 += rb) work.push_back(make_int2(t, r0));
         }
         lv.nwork = (int)work.size();
         HSS_TRY(upload(c, lv.up_items, up));
@@ -403,15 +421,17 @@ int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm) {
         HIP_TRY(hipMemcpyAsync(ll.bvec.p, b_perm, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
-        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork));
+        if (lv.skip) continue;
+        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec));
     }
     {
         Level& rl = c->lev[0];
-        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork));
+        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.vec));
     }
     for (int l = 1; l <= L; ++l) {
         Level& lv = c->lev[l];
-        HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork));
+        if (lv.skip) continue;
+        HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec));
     }
     if (x_perm != ll.xvec.as<double>())
         HIP_TRY(hipMemcpyAsync(x_perm, ll.xvec.p, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
