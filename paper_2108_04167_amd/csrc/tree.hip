@@ -9,30 +9,45 @@
 
 namespace {
 
-void split_node(const double* F, int r, int64_t* idx, int64_t cnt) {
+struct KeyIdx {
+    double  v;
+    int64_t i;
+};
+
+// Variance of every coordinate over the node in two row-major passes (mean, then squared deviations, both
+// summed in the node's current point order), then a sort of (value, original index) pairs.
+void split_node(const double* F, int r, int64_t* idx, int64_t cnt, std::vector<double>& mean, std::vector<double>& var,
+                std::vector<KeyIdx>& keys) {
+    mean.assign(r, 0.0);
+    var.assign(r, 0.0);
+    for (int64_t i = 0; i < cnt; ++i) {
+        const double* f = F + idx[i] * r;
+        for (int c = 0; c < r; ++c) mean[c] += f[c];
+    }
+    for (int c = 0; c < r; ++c) mean[c] /= (double)cnt;
+    for (int64_t i = 0; i < cnt; ++i) {
+        const double* f = F + idx[i] * r;
+        for (int c = 0; c < r; ++c) {
+            const double d = f[c] - mean[c];
+            var[c] += d * d;
+        }
+    }
     int best = 0;
     double bestv = -1.0;
     for (int c = 0; c < r; ++c) {
-        double mean = 0.0;
-        for (int64_t i = 0; i < cnt; ++i) mean += F[idx[i] * r + c];
-        mean /= (double)cnt;
-        double var = 0.0;
-        for (int64_t i = 0; i < cnt; ++i) {
-            double d = F[idx[i] * r + c] - mean;
-            var += d * d;
-        }
-        var /= (double)cnt;
-        if (var > bestv) {
-            bestv = var;
+        const double v = var[c] / (double)cnt;
+        if (v > bestv) {
+            bestv = v;
             best = c;
         }
     }
-    const int c = best;
-    std::sort(idx, idx + cnt, [F, r, c](int64_t a, int64_t b) {
-        double va = F[a * r + c], vb = F[b * r + c];
-        if (va != vb) return va < vb;
-        return a < b;
+    keys.resize(cnt);
+    for (int64_t i = 0; i < cnt; ++i) keys[i] = KeyIdx{F[idx[i] * r + best], idx[i]};
+    std::sort(keys.begin(), keys.end(), [](const KeyIdx& a, const KeyIdx& b) {
+        if (a.v != b.v) return a.v < b.v;
+        return a.i < b.i;
     });
+    for (int64_t i = 0; i < cnt; ++i) idx[i] = keys[i].i;
 }
 
 }  // namespace
@@ -45,14 +60,18 @@ int build_cluster_tree(const double* F_host, int64_t n, int r, int leaf, int64_t
     for (int64_t width = n; width > leaf; width /= 2) {
         const int64_t nodes = n / width;
         if (nodes == 1 || nthreads <= 1) {
-            for (int64_t t = 0; t < nodes; ++t) split_node(F_host, r, perm + t * width, width);
+            std::vector<double> mean, var;
+            std::vector<KeyIdx> keys;
+            for (int64_t t = 0; t < nodes; ++t) split_node(F_host, r, perm + t * width, width, mean, var, keys);
         } else {
             const int nt = (int)std::min<int64_t>(nthreads, nodes);
             std::vector<std::thread> th;
             th.reserve(nt);
             for (int w = 0; w < nt; ++w)
                 th.emplace_back([=]() {
-                    for (int64_t t = w; t < nodes; t += nt) split_node(F_host, r, perm + t * width, width);
+                    std::vector<double> mean, var;
+                    std::vector<KeyIdx> keys;
+                    for (int64_t t = w; t < nodes; t += nt) split_node(F_host, r, perm + t * width, width, mean, var, keys);
                 });
             for (auto& x : th) x.join();
         }

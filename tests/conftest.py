@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(autouse=True, scope="session")
+def _few_blas_threads():
+    """The oracle multiplies and factors many small blocks; with one BLAS thread per core these calls spend
+    their time handing work between threads (measured: 25x slower with 8 threads than with 1 on 256 x 256
+    blocks).  Four threads keep the large products fast and the small ones cheap.  The oracle itself is not
+    changed by this."""
+    try:
+        from threadpoolctl import threadpool_limits
+    except ImportError:
+        yield
+        return
+    with threadpool_limits(limits=4):
+        yield

@@ -1,0 +1,189 @@
+"""Parity at the full workload sizes, in the launch configuration the benchmark times (GPU only).
+
+cfg2 (n = 65 536) and cfg3 (n = 262 144, the benchmark's workload): sampled rows of S = K Omega against the
+oracle, then the exported compressed matrix goes through the oracle's ULV factorization, solve and ADMM
+(same staging as tests/test_gpu_path.py).  cfg4 (n = 1 048 576) and cfg5 (n = 262 144, r = 90): the oracle
+cannot factor in test time, so the solve is checked through a property that holds at any size -- the
+residual of (K~ + delta I + beta I) x = b evaluated with the ORACLE's HSS mat-vec on the exported generators --
+plus the invariants of the ADMM iterates.
+"""
+import ctypes as C
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import admm as oadmm          # noqa: E402
+from oracle import hss as ohss            # noqa: E402
+from oracle import ulv as oulv            # noqa: E402
+from oracle.kernel import gaussian_kernel  # noqa: E402
+from oracle.tree import cluster_tree      # noqa: E402
+from paper_2108_04167_amd import binding, synth   # noqa: E402
+
+
+def _dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+_T0 = time.time()
+
+
+def _say(msg):
+    """Progress line (visible with pytest -s): the oracle legs are silent for a while otherwise."""
+    print(f"[fullsize +{time.time() - _T0:6.0f}s] {msg}", flush=True)
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _library_omega(n, s, seed=0):
+    """The Omega hss_compress draws for this seed (through the library's generator hook)."""
+    import torch
+    from gpu_helpers import lib, ptr
+    L = lib()
+    Om = torch.empty((n, s), dtype=torch.float64, device="cuda:0")
+    L.hsx_omega.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_uint64]
+    assert L.hsx_omega(None, ptr(Om), n, s, seed) == 0
+    return Om
+
+
+def _check_sampled_rows(ctx, w, Om_dev, nrows, seed):
+    """S = K Omega on the GPU (all rows) against the oracle on a few rows computed one block at a time."""
+    F = _dev(w.F)
+    S = ctx.hss_kernel_sample(F, w.h, Om_dev)
+    rows = np.random.default_rng(seed).choice(w.n, nrows, replace=False)
+    Om = Om_dev.cpu().numpy()
+    ref = gaussian_kernel(w.F[rows], w.F, w.h) @ Om
+    got = S[_dev(rows)].cpu().numpy()
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= 1e-12 * scale
+    del S
+
+
+def _full_oracle_parity(w, admm_iters):
+    from gpu_helpers import oracle_hss_from_export
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", w.s)
+    F, y = _dev(w.F), _dev(w.y)
+    Om = _library_omega(w.n, w.s)
+    _say(f"{w.name}: sampled rows of S")
+    _check_sampled_rows(ctx, w, Om, 16, 1)
+    del Om
+    _say("compress")
+    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)            # in-library Omega: the benchmark's path
+    assert rc >= 0
+    _say("export")
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    _say("oracle tree")
+    assert np.array_equal(perm, cluster_tree(w.F, w.leaf))
+    H = oracle_hss_from_export(exp)
+    i = w.n // w.leaf // 3
+    blk = slice(i * w.leaf, (i + 1) * w.leaf)
+    Fp = w.F[perm]
+    assert np.abs(exp["D"][i] - gaussian_kernel(Fp[blk], Fp[blk], w.h)).max() <= 1e-14
+    # P2: ULV solve on the same compressed matrix
+    ctx.hss_ulv_factor(w.beta)
+    rng = np.random.default_rng(3)
+    b = rng.standard_normal(w.n)
+    x = _dev(b)
+    ctx.hss_ulv_solve(x)
+    x = x.cpu().numpy()
+    _say("oracle ULV factor")
+    Fz = oulv.ulv_factor(H, w.beta)
+    _say("oracle ULV solve")
+    ref = np.empty(w.n)
+    ref[perm] = oulv.ulv_solve(Fz, b[perm])
+    assert _rel(x, ref) <= 1e-10, _rel(x, ref)
+    # mat-vec
+    yv = ctx.hss_matvec(_dev(b)).cpu().numpy()
+    mref = np.empty(w.n)
+    mref[perm] = ohss.matvec(H, b[perm])
+    assert _rel(yv, mref) <= 1e-12
+    # P3: ADMM on the same compressed matrix
+    _say("ADMM")
+    out = ctx.admm_svm_train(w.C, w.beta, admm_iters)
+    yp = w.y[perm]
+    oref = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), yp, w.C, w.beta, admm_iters)
+    for key in ("x", "z", "mu"):
+        got = out[key].cpu().numpy()[perm]
+        assert _rel(got, oref[key]) <= 1e-6, (key, _rel(got, oref[key]))
+    _say("bias / decision")
+    b_ref, cnt_ref = oadmm.bias(oref["z"], yp, w.C, lambda v: ohss.matvec(H, v))
+    if out["n_margin"] == cnt_ref:
+        assert abs(out["bias"] - b_ref) <= 1e-6 * max(1.0, abs(b_ref))
+    # label assignment on a slice of the test set
+    G = w.F_test[:512]
+    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
+    dec_ref = oadmm.decision(Fp, yp, oref["z"], out["bias"], G, w.h)
+    assert np.abs(dec - dec_ref).max() <= 1e-6 * max(1.0, np.abs(dec_ref).max())
+    assert abs(oadmm.accuracy(dec, w.y_test[:512]) - oadmm.accuracy(dec_ref, w.y_test[:512])) <= 0.1
+    ctx.close()
+
+
+def test_cfg2_full_size_against_oracle():
+    _full_oracle_parity(synth.make_workload(2), admm_iters=25)
+
+
+def test_cfg3_full_size_against_oracle():
+    t0 = time.time()
+    _full_oracle_parity(synth.make_workload(3), admm_iters=6)
+    print(f"cfg3 full-size parity took {time.time() - t0:.0f} s")
+
+
+def _property_parity(w, admm_iters, sweep=False):
+    from gpu_helpers import oracle_hss_from_export
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", w.s)
+    F, y = _dev(w.F), _dev(w.y)
+    _say(f"{w.name}: compress")
+    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)
+    assert rc >= 0
+    st = ctx.hss_stats()
+    _say("export")
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    H = oracle_hss_from_export(exp)
+    del exp
+    rng = np.random.default_rng(5)
+    b = rng.standard_normal(w.n)
+    betas = w.beta_grid if sweep else (w.beta,)
+    for beta in betas:
+        _say(f"factor/solve beta={beta}")
+        ctx.hss_ulv_factor(beta)
+        x = _dev(b)
+        ctx.hss_ulv_solve(x)
+        x = x.cpu().numpy()
+        # residual with the oracle's mat-vec: (K~ + delta I) x + beta x = b
+        r = ohss.matvec(H, x[perm]) + beta * x[perm] - b[perm]
+        # the matrix is symmetric positive definite with lambda_min >= ~beta, so the error is bounded by the
+        # residual over beta
+        assert np.linalg.norm(r) <= 1e-10 * beta * np.linalg.norm(x), (beta, np.linalg.norm(r) / np.linalg.norm(x))
+    _say("ADMM")
+    out = ctx.admm_svm_train(w.C, betas[-1], admm_iters)
+    xg, zg = out["x"].cpu().numpy(), out["z"].cpu().numpy()
+    assert zg.min() >= 0.0 and zg.max() <= w.C
+    assert abs(float(w.y @ xg)) <= 1e-9 * max(1.0, np.linalg.norm(xg))          # y^T x^k = 0 (Sec. 2.1)
+    mu = out["mu"].cpu().numpy()
+    # z^{k+1} = clip(x^{k+1} - mu^k / beta) and mu^{k+1} = mu^k - beta (x - z): eliminate mu^k
+    beta = betas[-1]
+    muk = mu + beta * (xg - zg)
+    assert np.abs(zg - np.clip(xg - muk / beta, 0.0, w.C)).max() <= 1e-12 * max(1.0, np.abs(xg).max())
+    # bias from the library's own iterate with the oracle's formula and mat-vec
+    b_own, cnt_own = oadmm.bias(zg[perm], w.y[perm], w.C, lambda v: ohss.matvec(H, v))
+    assert out["n_margin"] == cnt_own
+    assert abs(out["bias"] - b_own) <= 1e-6 * max(1.0, abs(b_own))
+    assert st["rank_max"] <= st["rank_cap"]
+    ctx.close()
+
+
+def test_cfg5_full_size_properties_and_beta_sweep():
+    _property_parity(synth.make_workload(5), admm_iters=30, sweep=True)
+
+
+def test_cfg4_full_size_properties():
+    _property_parity(synth.make_workload(4), admm_iters=20)
