@@ -12,7 +12,22 @@ __global__ void probe_mfma_kernel(const double* a, const double* b, double* d) {
 }
 }  // namespace
 
+__global__ __launch_bounds__(256) void plain_copy_kernel(const double2* __restrict__ src, double2* __restrict__ dst,
+                                                         size_t n2) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n2; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 extern "C" {
+
+// dst[0..n) = src[0..n) (n even, 16-byte aligned pointers): a plain streaming copy of known size, the
+// reference that turns the memory counters' raw readings into bytes.
+int hsx_plain_copy(void* stream, const double* src_dev, double* dst_dev, int64_t n) {
+    if (n <= 0 || (n & 1)) return HSS_EINVAL;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const double2*)src_dev,
+                       (double2*)dst_dev, (size_t)n / 2);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
 
 // d[l*4+v] = accumulator register v of lane l after one 16x16x4 f64 MFMA with per-lane operands a[l], b[l].
 int hsx_probe_mfma(const double* a_dev, const double* b_dev, double* d_dev) {

@@ -3,6 +3,10 @@
 // a plain executable; the measured kernels and launch shapes are those of the library.
 //
 //   hss_bench_native n r s leaf h maxit [nsolve]
+//
+// After the library calls it runs the library's plain_copy_kernel three times on 2^27 doubles (1 GiB read,
+// 1 GiB written per launch): the reference that converts the memory counters' raw readings into bytes.
+// All device code lives in the library: the executable itself carries no kernel.
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -13,6 +17,8 @@
 #include <vector>
 
 #include "../../include/hss_svm.h"
+
+extern "C" int hsx_plain_copy(void* stream, const double* src_dev, double* dst_dev, int64_t n);   // library test hook
 
 static uint64_t splitmix(uint64_t& s) {
     s += 0x9E3779B97F4A7C15ull;
@@ -86,6 +92,21 @@ int main(int argc, char** argv) {
            (t3 - t2) / nsolve * 1e3, st.factor_bytes / ((t3 - t2) / nsolve) / 1e9, maxit, t4 - t3, bias, (long long)nm,
            st.delta);
     hss_destroy(ctx);
+    {
+        const size_t nd = (size_t)1 << 27;
+        double *a = nullptr, *b = nullptr;
+        if (hipMalloc(&a, nd * sizeof(double)) != hipSuccess || hipMalloc(&b, nd * sizeof(double)) != hipSuccess) return 1;
+        hipMemset(a, 0, nd * sizeof(double));
+        hipMemset(b, 0, nd * sizeof(double));
+        hipDeviceSynchronize();
+        double tc = now();
+        for (int i = 0; i < 3; ++i) CHECK(hsx_plain_copy(nullptr, a, b, (int64_t)nd));
+        if (hipDeviceSynchronize() != hipSuccess) return 1;
+        printf("plain_copy_kernel: %.1f GB/s (read + write, 3 launches of 2 x 1 GiB)\n",
+               3.0 * 2.0 * nd * sizeof(double) / (now() - tc) / 1e9);
+        hipFree(a);
+        hipFree(b);
+    }
     hipFree(dF);
     hipFree(dy);
     hipFree(dx);
