@@ -3,16 +3,21 @@
 The paper only says that the points are clustered/reordered before compression
 so that off-diagonal blocks become low-rank (Sec. 1.2, first bullet; Fig. 1).
 The reading used here: a perfect binary tree; a node's points are split at the
-median of the coordinate with the largest variance over the node.
+median of the coordinate with the largest variance over the node.  Variances
+within a relative 1e-9 of the largest count as equal (the lowest coordinate
+wins), so that the choice does not hinge on the rounding of a sum -- columns
+standardised to unit variance differ only by that.
 """
 import numpy as np
+
+TIE = 1e-9   # relative width of a tie between variances
 
 
 def cluster_tree(F, leaf):
     """Return perm (int64, length n): the points in leaf order, left to right.
 
-    Node rule: c = coordinate of largest population variance over the node
-    (ties -> lowest coordinate index); sort the node's points by
+    Node rule: c = lowest coordinate whose population variance over the node
+    is at least (1 - 1e-9) times the largest one; sort the node's points by
     (value of coordinate c, original index); lower half -> left child, upper
     half -> right child; stop when the node holds `leaf` points.
     n must equal leaf * 2^L.
@@ -30,7 +35,7 @@ def cluster_tree(F, leaf):
             return
         sub = F[idx]
         var = ((sub - sub.mean(axis=0)) ** 2).mean(axis=0)
-        c = int(np.argmax(var))                  # first maximum = lowest index on ties
+        c = int(np.flatnonzero(var >= var.max() * (1.0 - TIE))[0])
         order = np.lexsort((idx, sub[:, c]))     # primary key value, secondary original index
         idx = idx[order]
         half = idx.size // 2

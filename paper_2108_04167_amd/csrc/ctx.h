@@ -70,7 +70,7 @@ struct hss_ctx {
     int64_t generator_bytes = 0, factor_bytes = 0, factor_bytes_compact = 0;
 };
 
-int build_cluster_tree(const double* F_host, int64_t n, int r, int leaf, int64_t* perm);
+int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int64_t* perm_dev, int* bad_dev);
 
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,

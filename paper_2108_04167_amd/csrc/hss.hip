@@ -230,18 +230,20 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     HSS_TRY(c->partial.reserve(sizeof(double) * 4 * VEC_BLOCKS));
     HSS_TRY(c->scal.reserve(sizeof(double) * 16));
 
-    // ---- labels must be +-1; cluster tree on the host ----
+    // ---- labels must be +-1 (checked on the host copy); cluster tree on the device ----
     double t0 = wall();
-    std::vector<double> Fh((size_t)n * r), yh(n);
-    HIP_TRY(hipMemcpyAsync(Fh.data(), F, sizeof(double) * n * r, hipMemcpyDeviceToHost, st));
+    std::vector<double> yh(n);
     HIP_TRY(hipMemcpyAsync(yh.data(), y, sizeof(double) * n, hipMemcpyDeviceToHost, st));
+    HSS_TRY(c->perm.reserve(sizeof(int64_t) * n));
+    HSS_TRY(build_cluster_tree(st, F, n, r, leaf, c->perm.as<int64_t>(), c->flags.as<int>() + 3));
+    c->perm_host.resize(n);
+    int bad_f = 0;
+    HIP_TRY(hipMemcpyAsync(c->perm_host.data(), c->perm.p, sizeof(int64_t) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&bad_f, c->flags.as<int>() + 3, sizeof(int), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    if (bad_f) return HSS_EINVAL;   // a non-finite feature value
     for (int64_t i = 0; i < n; ++i)
         if (yh[i] != 1.0 && yh[i] != -1.0) return HSS_EINVAL;
-    c->perm_host.resize(n);
-    HSS_TRY(build_cluster_tree(Fh.data(), n, r, leaf, c->perm_host.data()));
-    HSS_TRY(c->perm.reserve(sizeof(int64_t) * n));
-    HIP_TRY(hipMemcpyAsync(c->perm.p, c->perm_host.data(), sizeof(int64_t) * n, hipMemcpyHostToDevice, st));
     const int64_t* perm = c->perm.as<int64_t>();
     HSS_TRY(c->Fp.reserve(sizeof(double) * n_pad * r_pad));
     HSS_TRY(c->nu.reserve(sizeof(double) * n_pad));

@@ -231,6 +231,12 @@ def test_error_paths():
     with pytest.raises(binding.HssError) as e:
         ctx.hss_compress(F, ybad, w.h, w.leaf, w.tol, _dev(w.omega()))
     assert e.value.code == binding.HSS_EINVAL
+    for badval in (float("nan"), float("inf")):
+        Fbad = F.clone()
+        Fbad[200, w.r - 1] = badval
+        with pytest.raises(binding.HssError) as e:
+            ctx.hss_compress(Fbad, y, w.h, w.leaf, w.tol, _dev(w.omega()))
+        assert e.value.code == binding.HSS_EINVAL
     ctx.hss_compress(F, y, w.h, w.leaf, w.tol, _dev(w.omega()))
     ctx.n = w.n
     with pytest.raises(binding.HssError) as e:

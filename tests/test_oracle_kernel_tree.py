@@ -72,6 +72,20 @@ def test_tree_ties_are_broken_by_index():
     assert np.array_equal(perm, np.arange(64))
 
 
+def test_tree_variances_equal_up_to_rounding_count_as_tied():
+    # column 1 is a shuffled copy of column 0 scaled by 1 + 1e-12: its variance is larger, but only at the
+    # level of a sum's rounding -> the lowest coordinate is taken; a relative excess of 1e-6 is a real difference
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal(256)
+    for scale, coord in ((1.0 + 1e-12, 0), (1.0 + 1e-6, 1)):
+        F = np.stack([x, rng.permutation(x) * scale], axis=1)
+        perm = cluster_tree(F, 128)
+        left, right = perm[:128], perm[128:]
+        assert F[left, coord].max() <= F[right, coord].min()
+        other = 1 - coord
+        assert F[left, other].max() > F[right, other].min()
+
+
 def test_tree_rejects_bad_sizes():
     with pytest.raises(ValueError):
         cluster_tree(np.zeros((100, 2)), 32)
