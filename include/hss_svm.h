@@ -153,6 +153,20 @@ int hss_export_sizes(hss_ctx* ctx, int64_t* nnodes, int64_t* u_len, int64_t* j_l
 int hss_export(hss_ctx* ctx, int64_t* perm, int32_t* sizes, int32_t* ranks, double* D, double* U,
                int32_t* J, double* B, double* delta_out);
 
+/* The inverse of hss_export: puts the context into the compressed state from generators in HOST memory
+ * (same arrays, same layout and node order as hss_export writes), for the points F_dev (n x r) and labels
+ * y_dev in DEVICE memory and the kernel width h.  Nothing is sampled or decomposed and the definiteness
+ * guard does not run: the represented matrix is the HSS matrix of (D, U, B) plus delta I with the caller's
+ * delta >= 0 (Sec. 3.2: the compressed matrix depends on (F, h) only, so it can be computed once and kept).
+ * The arrays are copied; the caller keeps ownership.  Checked on the host: perm is a permutation of 0..n-1;
+ * sizes/ranks describe a perfect binary tree with leaf blocks of `leaf` rows, inner size = sum of the children's
+ * ranks, 1 <= rank <= size below the root and rank 0 at the root; every J lists distinct rows of its node and
+ * U is interpolative on them (row J_j of U_t is exactly the j-th unit vector); labels are +-1.  Violations return HSS_EINVAL, ranks above 512 HSS_EUNSUPPORTED; the context is then not
+ * compressed.  Returns 0 or HSS_WSHIFT (delta > 0).  Synchronous. */
+int hss_import(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,
+               const int64_t* perm, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
+               const int32_t* J, const double* B, double delta);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,6 +46,8 @@ ABI = {
     "hss_stats": (C.c_int, [C.c_void_p, C.POINTER(HssStats)]),
     "hss_export_sizes": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
     "hss_export": (C.c_int, [C.c_void_p, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, C.POINTER(C.c_double)]),
+    "hss_import": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32,
+                             c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, C.c_double]),
 }
 
 
@@ -212,3 +214,19 @@ class Context:
         return {"n": n, "leaf": leaf, "perm": perm, "sizes": sizes, "ranks": ranks,
                 "D": D.reshape(n // leaf, leaf, leaf), "U": U[:ul.value], "J": J[:jl.value], "B": B[:bl.value],
                 "delta": delta.value}
+
+    def hss_import(self, F, y, h, leaf, gen):
+        """Compressed state from host generators `gen` (a dict laid out like hss_export's result)."""
+        import numpy as np
+        n, r = F.shape
+        keep = [np.ascontiguousarray(gen["perm"], dtype=np.int64), np.ascontiguousarray(gen["sizes"], dtype=np.int32),
+                np.ascontiguousarray(gen["ranks"], dtype=np.int32),
+                np.ascontiguousarray(gen["D"], dtype=np.float64).reshape(-1),
+                np.ascontiguousarray(gen["U"], dtype=np.float64), np.ascontiguousarray(gen["J"], dtype=np.int32),
+                np.ascontiguousarray(gen["B"], dtype=np.float64)]
+        keep = [a if a.size else np.zeros(1, dtype=a.dtype) for a in keep]
+        p = lambda a: C.c_void_p(a.ctypes.data)
+        rc = _check(_lib.hss_import(self._h, _ptr(F), _ptr(y), n, r, float(h), int(leaf), *[p(a) for a in keep],
+                                    float(gen.get("delta", 0.0))), "hss_import")
+        self.n, self.r = n, r
+        return rc

@@ -85,6 +85,12 @@ int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y
     return hss_compress_impl(ctx, F_dev, y_dev, n, r, h, leaf, tol, Omega_dev, s);
 }
 
+int hss_import(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,
+               const int64_t* perm, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
+               const int32_t* J, const double* B, double delta) {
+    return hss_import_impl(ctx, F_dev, y_dev, n, r, h, leaf, perm, sizes, ranks, D, U, J, B, delta);
+}
+
 int hss_ulv_factor(hss_ctx* ctx, double beta) { return ulv_factor_impl(ctx, beta); }
 
 int hss_ulv_solve(hss_ctx* c, double* rhs, int32_t nrhs) {

@@ -75,6 +75,9 @@ int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, in
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
                       const double* Omega, int s_in);
+int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf,
+                    const int64_t* perm_h, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
+                    const int32_t* J, const double* B, double delta);
 int hss_matvec_perm(hss_ctx* c);           // mv_y = K~' mv_x  (cluster-tree order, shift included)
 // ulv.hip
 int ulv_factor_impl(hss_ctx* c, double beta);

@@ -444,3 +444,162 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->t_guard = wall() - t0;
     return c->warnings;
 }
+
+// Rebuilds a compressed context from generators in host memory (the arrays hss_export writes, or those of
+// any other construction of the same HSS form): no sampling, no interpolative decompositions, no guard --
+// the caller's delta is taken as given.
+int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf,
+                    const int64_t* perm_h, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
+                    const int32_t* J, const double* B, double delta) {
+    if (!c || !F || !y || !perm_h || !sizes || !ranks || !D || !U || !J || !B) return HSS_EINVAL;
+    if (n < 1 || r < 1 || !(h > 0.0) || !(delta >= 0.0) || !(delta <= 1.7976931348623157e308)) return HSS_EINVAL;
+    if (leaf < 16 || leaf % 16 != 0 || n % leaf != 0) return HSS_EINVAL;
+    const int64_t nl = n / leaf;
+    if (nl & (nl - 1)) return HSS_EINVAL;
+    if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
+    int L = 0;
+    while ((int64_t(1) << L) < nl) ++L;
+    // ---- host-side validation of the tree arrays ----
+    {
+        std::vector<char> seen(n, 0);
+        for (int64_t i = 0; i < n; ++i) {
+            if (perm_h[i] < 0 || perm_h[i] >= n || seen[perm_h[i]]) return HSS_EINVAL;
+            seen[perm_h[i]] = 1;
+        }
+    }
+    int kmax = 0;
+    {
+        int64_t jo = 0, uo = 0;
+        std::vector<char> mark;
+        for (int l = 0; l <= L; ++l)
+            for (int64_t t = 0; t < (int64_t(1) << l); ++t) {
+                const int64_t node = (int64_t(1) << l) - 1 + t;
+                const int m = sizes[node], k = ranks[node];
+                if (l == L ? m != leaf : m != ranks[2 * node + 1] + ranks[2 * node + 2]) return HSS_EINVAL;
+                if (l == 0) {
+                    if (k != 0) return HSS_EINVAL;
+                    continue;
+                }
+                if (k < 1 || k > m) return HSS_EINVAL;
+                if (k > 512 || m > 1024) return HSS_EUNSUPPORTED;
+                kmax = std::max(kmax, k);
+                mark.assign(m, 0);
+                for (int j = 0; j < k; ++j) {      // skeleton rows: distinct, inside the node
+                    const int v = J[jo + j];
+                    if (v < 0 || v >= m || mark[v]) return HSS_EINVAL;
+                    mark[v] = 1;
+                    // interpolative basis: row J_j of U is the j-th unit vector (the factorization relies on it)
+                    const double* urow = U + uo + (int64_t)v * k;
+                    for (int q = 0; q < k; ++q)
+                        if (urow[q] != (q == j ? 1.0 : 0.0)) return HSS_EINVAL;
+                }
+                jo += k;
+                uo += (int64_t)m * k;
+            }
+    }
+    hipStream_t st = c->stream;
+    c->compressed = c->factored = false;
+    c->lev.clear();
+    c->lev.resize(L + 1);
+    c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = 0; c->s_pad = 0; c->kcap = std::max(kmax, 1);
+    c->h = h; c->tol = 0.0; c->delta = delta; c->beta = -1.0; c->warnings = delta > 0.0 ? HSS_WSHIFT : 0;
+    c->r_pad = feature_pad(r);
+    c->n_pad = round_up(n, 256);
+    c->t_tree = c->t_sample = c->t_levels = c->t_guard = c->t_sample_kernel = 0.0;
+    c->sample_flops = 0.0;
+    if (!c->arena.h) HSS_TRY(c->arena.init(size_t(96) << 20));
+    c->arena.reset();
+    HSS_TRY(c->flags.reserve(sizeof(int) * 4));
+    HIP_TRY(hipMemsetAsync(c->flags.p, 0, sizeof(int) * 4, st));
+    HSS_TRY(c->partial.reserve(sizeof(double) * 4 * VEC_BLOCKS));
+    HSS_TRY(c->scal.reserve(sizeof(double) * 16));
+    std::vector<double> yh(n);
+    HIP_TRY(hipMemcpyAsync(yh.data(), y, sizeof(double) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int64_t i = 0; i < n; ++i)
+        if (yh[i] != 1.0 && yh[i] != -1.0) return HSS_EINVAL;
+    c->perm_host.assign(perm_h, perm_h + n);
+    HSS_TRY(c->perm.reserve(sizeof(int64_t) * n));
+    HIP_TRY(hipMemcpyAsync(c->perm.p, perm_h, sizeof(int64_t) * n, hipMemcpyHostToDevice, st));
+    const int64_t* perm = c->perm.as<int64_t>();
+    HSS_TRY(c->Fp.reserve(sizeof(double) * c->n_pad * c->r_pad));
+    HSS_TRY(c->nu.reserve(sizeof(double) * c->n_pad));
+    HSS_TRY(c->yp.reserve(sizeof(double) * n));
+    HSS_TRY(gather_pad_rows_launch(st, F, perm, c->Fp.as<double>(), n, c->n_pad, r, c->r_pad));
+    HSS_TRY(row_norms_launch(st, c->Fp.as<double>(), c->nu.as<double>(), c->n_pad, c->r_pad));
+    HSS_TRY(vec_gather(st, c->yp.as<double>(), y, perm, n));
+    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)n * leaf));
+    HIP_TRY(hipMemcpyAsync(c->Dleaf.p, D, sizeof(double) * (size_t)n * leaf, hipMemcpyHostToDevice, st));
+    // ---- levels: sizes, offsets, generators; skeleton points rebuilt from the skeleton rows ----
+    int64_t uo = 0, jo = 0, bo = 0;
+    std::vector<std::vector<int64_t>> skel(L + 1);
+    for (int l = 0; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        lv.N = 1 << l;
+        const int64_t first = (int64_t(1) << l) - 1;
+        lv.msz.assign(sizes + first, sizes + first + lv.N);
+        lv.rk.assign(ranks + first, ranks + first + lv.N);
+        lv.moff.assign(lv.N + 1, 0);
+        lv.koff.assign(lv.N + 1, 0);
+        lv.uoff.assign(lv.N + 1, 0);
+        lv.maxm = lv.maxk = 0;
+        for (int t = 0; t < lv.N; ++t) {
+            lv.moff[t + 1] = lv.moff[t] + lv.msz[t];
+            lv.koff[t + 1] = lv.koff[t] + lv.rk[t];
+            lv.uoff[t + 1] = lv.uoff[t] + (int64_t)lv.msz[t] * lv.rk[t];
+            lv.maxm = std::max(lv.maxm, lv.msz[t]);
+            lv.maxk = std::max(lv.maxk, lv.rk[t]);
+        }
+        if (l >= 1) {
+            HSS_TRY(upload(c, lv.d_moff, lv.moff));
+            HSS_TRY(upload(c, lv.d_koff, lv.koff));
+            HSS_TRY(upload(c, lv.d_uoff, lv.uoff));
+            HSS_TRY(lv.U.reserve(sizeof(double) * std::max<int64_t>(lv.uoff[lv.N], 1)));
+            HSS_TRY(lv.J.reserve(sizeof(int) * std::max<int64_t>(lv.koff[lv.N], 1)));
+            HIP_TRY(hipMemcpyAsync(lv.U.p, U + uo, sizeof(double) * lv.uoff[lv.N], hipMemcpyHostToDevice, st));
+            HIP_TRY(hipMemcpyAsync(lv.J.p, J + jo, sizeof(int) * lv.koff[lv.N], hipMemcpyHostToDevice, st));
+            uo += lv.uoff[lv.N];
+            jo += lv.koff[lv.N];
+        }
+        if (l < L) {
+            lv.boff.assign(lv.N + 1, 0);
+            for (int t = 0; t < lv.N; ++t) {
+                const int64_t node = first + t;
+                lv.boff[t + 1] = lv.boff[t] + (int64_t)ranks[2 * node + 1] * ranks[2 * node + 2];
+            }
+            HSS_TRY(lv.B.reserve(sizeof(double) * std::max<int64_t>(lv.boff[lv.N], 1)));
+            HIP_TRY(hipMemcpyAsync(lv.B.p, B + bo, sizeof(double) * lv.boff[lv.N], hipMemcpyHostToDevice, st));
+            bo += lv.boff[lv.N];
+        }
+    }
+    {
+        int64_t jbase = 0;
+        std::vector<int64_t> joff(L + 2, 0);   // start of each level's block in J (heap order = level order)
+        for (int l = 1; l <= L; ++l) {
+            joff[l] = jbase;
+            jbase += c->lev[l].koff[c->lev[l].N];
+        }
+        for (int l = L; l >= 1; --l) {
+            Level& lv = c->lev[l];
+            skel[l].resize(lv.koff[lv.N]);
+            for (int t = 0; t < lv.N; ++t)
+                for (int j = 0; j < lv.rk[t]; ++j) {
+                    const int row = J[joff[l] + lv.koff[t] + j];
+                    // rows of an inner node = the children's skeleton points, left child first
+                    skel[l][lv.koff[t] + j] = l == L ? lv.moff[t] + row : skel[l + 1][c->lev[l + 1].koff[2 * t] + row];
+                }
+            HSS_TRY(lv.skel.reserve(sizeof(int64_t) * std::max<int64_t>(lv.koff[lv.N], 1)));
+            HIP_TRY(hipMemcpyAsync(lv.skel.p, skel[l].data(), sizeof(int64_t) * skel[l].size(), hipMemcpyHostToDevice, st));
+        }
+    }
+    c->generator_bytes = (int64_t)sizeof(double) * n * leaf;
+    for (int l = 0; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        if (l >= 1) c->generator_bytes += (int64_t)sizeof(double) * lv.uoff[lv.N];
+        if (l < L) c->generator_bytes += (int64_t)sizeof(double) * lv.boff[lv.N];
+    }
+    HIP_TRY(hipStreamSynchronize(st));     // host staging (skel, the caller's arrays) may go away after return
+    HSS_TRY(build_matvec_tables(c));
+    c->compressed = true;
+    return c->warnings;
+}

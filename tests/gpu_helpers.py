@@ -46,3 +46,17 @@ def oracle_hss_from_export(exp, with_shift=True):
     H.D = [exp["D"][i] + shift * np.eye(leaf) for i in range(n // leaf)]
     assert uo == exp["U"].size and bo == exp["B"].size
     return H
+
+
+def export_from_oracle_hss(H, perm, delta=0.0):
+    """The oracle's generators in the layout hss_export writes / hss_import reads (D without the shift)."""
+    nn = H.nnodes
+    sizes = np.array([H.size(t) for t in range(nn)], dtype=np.int32)
+    ranks = np.array([H.rank(t) for t in range(nn)], dtype=np.int32)
+    U = [H.U[t].reshape(-1) for t in range(1, nn)]
+    J = [np.asarray(H.J[t], dtype=np.int32) for t in range(1, nn)]
+    B = [H.B[t].reshape(-1) for t in range(H.first_leaf())]
+    cat = lambda xs, dt: np.concatenate(xs).astype(dt) if xs else np.zeros(0, dtype=dt)
+    return {"n": H.n, "leaf": H.leaf, "perm": np.asarray(perm, dtype=np.int64), "sizes": sizes, "ranks": ranks,
+            "D": np.stack(H.D), "U": cat(U, np.float64), "J": cat(J, np.int32), "B": cat(B, np.float64),
+            "delta": float(delta)}
