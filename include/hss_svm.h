@@ -99,7 +99,7 @@ int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y
 int hss_ulv_factor(hss_ctx* ctx, double beta);
 
 /* rhs <- (K~ + beta I)^{-1} rhs, in place.  rhs (dev, n x nrhs, column-major: each right-hand side is
- * a contiguous n-vector).  nrhs >= 1. */
+ * a contiguous n-vector).  nrhs >= 1; up to four right-hand sides share one pass over the factors. */
 int hss_ulv_solve(hss_ctx* ctx, double* rhs_inout_dev, int32_t nrhs);
 
 /* y_out <- K~ x (with the guard's diagonal shift included).  x, y_out (dev, n); may not alias. */
@@ -113,6 +113,17 @@ int hss_matvec(hss_ctx* ctx, const double* x_dev, double* y_out_dev);
 int admm_svm_train(hss_ctx* ctx, double C, double beta, int32_t maxit,
                    double* x_out_dev, double* z_out_dev, double* mu_out_dev,
                    double* bias_out_host, int64_t* n_margin_out_host);
+
+/* The same for nC box bounds C_list[0..nC) (host) and one beta: the hyper-parameter sweep the caching of
+ * Sec. 3.2 is meant for (compression once per h, factorization once per beta, then one ADMM run per C).
+ * The runs are independent and share the factorization, w = Y K_beta^{-1} e and w1; they advance in lockstep,
+ * up to four at a time as interleaved right-hand sides of one ULV sweep, so the factors are read once per
+ * iteration for four runs.  Every run's iterates equal those of admm_svm_train with that C.
+ * x_out, z_out, mu_out (dev, nC x n, run j at offset j*n; any may be null); bias_out, n_margin_out
+ * (host, nC entries; may be null).  Returns the OR of the runs' warnings. */
+int admm_svm_train_multi(hss_ctx* ctx, const double* C_list, int32_t nC, double beta, int32_t maxit,
+                         double* x_out_dev, double* z_out_dev, double* mu_out_dev,
+                         double* bias_out, int64_t* n_margin_out);
 
 /* dec_j = sum_i y_i z_i K(f_i, g_j) + bias with the exact kernel (label loop of Algorithm 3).
  * G (dev, n_test x r), z (dev, n), dec_out (dev, n_test). */

@@ -42,6 +42,8 @@ ABI = {
     "hss_matvec": (C.c_int, [C.c_void_p, c_dp, c_dp]),
     "admm_svm_train": (C.c_int, [C.c_void_p, C.c_double, C.c_double, C.c_int32, c_dp, c_dp, c_dp,
                                  C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "admm_svm_train_multi": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_int32, C.c_double, C.c_int32, c_dp, c_dp,
+                                       c_dp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "svm_decision": (C.c_int, [C.c_void_p, c_dp, C.c_int64, c_dp, C.c_double, c_dp]),
     "hss_stats": (C.c_int, [C.c_void_p, C.POINTER(HssStats)]),
     "hss_export_sizes": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
@@ -230,3 +232,18 @@ class Context:
                                     float(gen.get("delta", 0.0))), "hss_import")
         self.n, self.r = n, r
         return rc
+
+    def admm_svm_train_multi(self, C_list, beta, maxit):
+        """One ADMM run per box bound in C_list (same beta); x, z, mu come back as (len(C_list), n)."""
+        import torch
+        nC = len(C_list)
+        cl = (C.c_double * nC)(*[float(v) for v in C_list])
+        dev = torch.device("cuda", torch.cuda.current_device())
+        x = torch.empty((nC, self.n), dtype=torch.float64, device=dev)
+        z = torch.empty_like(x)
+        mu = torch.empty_like(x)
+        bias = (C.c_double * nC)()
+        cnt = (C.c_int64 * nC)()
+        rc = _check(_lib.admm_svm_train_multi(self._h, cl, nC, float(beta), int(maxit), _ptr(x), _ptr(z), _ptr(mu),
+                                              bias, cnt), "admm_svm_train_multi")
+        return {"x": x, "z": z, "mu": mu, "bias": list(bias), "n_margin": list(cnt), "warnings": rc}

@@ -97,13 +97,16 @@ int hss_ulv_solve(hss_ctx* c, double* rhs, int32_t nrhs) {
     if (!c || !rhs || nrhs < 1) return HSS_EINVAL;
     if (!c->compressed || !c->factored) return HSS_ESTATE;
     hipStream_t st = c->stream;
-    Level& ll = c->lev[c->L];
     const int64_t* perm = c->perm.as<int64_t>();
-    for (int j = 0; j < nrhs; ++j) {
-        double* col = rhs + (size_t)j * c->n;
-        HSS_TRY(vec_gather(st, ll.bvec.as<double>(), col, perm, c->n));
-        HSS_TRY(ulv_solve_perm(c, ll.bvec.as<double>(), ll.xvec.as<double>()));
-        HSS_TRY(vec_scatter(st, col, ll.xvec.as<double>(), perm, c->n));
+    // groups of up to MAX_NRHS columns share one pass over the factors
+    for (int j0 = 0; j0 < nrhs;) {
+        const int g = std::min(nrhs - j0, MAX_NRHS);
+        const int nr = g == 1 ? 1 : (g == 2 ? 2 : 4);
+        double* cols = rhs + (size_t)j0 * c->n;
+        HSS_TRY(vec_gather_cols(st, solve_rhs(c), cols, perm, c->n, nr, g));
+        HSS_TRY(ulv_solve_inplace(c, nr));
+        HSS_TRY(vec_scatter_cols(st, cols, solve_sol(c, nr), perm, c->n, nr, g));
+        j0 += g;
     }
     return HSS_OK;
 }
@@ -119,9 +122,11 @@ int hss_matvec(hss_ctx* c, const double* x, double* y) {
     return HSS_OK;
 }
 
-int admm_svm_train(hss_ctx* c, double C, double beta, int32_t maxit, double* x_out, double* z_out, double* mu_out,
-                   double* bias_out, int64_t* n_margin_out) {
-    if (!c || !(C > 0.0) || !(beta > 0.0) || maxit < 0) return HSS_EINVAL;
+int admm_svm_train_multi(hss_ctx* c, const double* C_list, int32_t nC, double beta, int32_t maxit, double* x_out,
+                         double* z_out, double* mu_out, double* bias_out, int64_t* n_margin_out) {
+    if (!c || !C_list || nC < 1 || !(beta > 0.0) || maxit < 0) return HSS_EINVAL;
+    for (int j = 0; j < nC; ++j)
+        if (!(C_list[j] > 0.0)) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
     int warn = 0;
     if (!c->factored || c->beta != beta) {
@@ -132,53 +137,79 @@ int admm_svm_train(hss_ctx* c, double C, double beta, int32_t maxit, double* x_o
     hipStream_t st = c->stream;
     const int64_t n = c->n;
     const size_t nb = sizeof(double) * n;
-    HSS_TRY(c->v_x.reserve(nb));
-    HSS_TRY(c->v_z.reserve(nb));
-    HSS_TRY(c->v_mu.reserve(nb));
+    const int width = nC == 1 ? 1 : (nC == 2 ? 2 : MAX_NRHS);
+    HSS_TRY(c->v_x.reserve(nb * width));
+    HSS_TRY(c->v_z.reserve(nb * width));
+    HSS_TRY(c->v_mu.reserve(nb * width));
     HSS_TRY(c->v_w.reserve(nb));
     HSS_TRY(c->v_e.reserve(nb));
-    Level& ll = c->lev[c->L];
-    double* rhs = ll.bvec.as<double>();
-    double* sol = ll.xvec.as<double>();
+    HSS_TRY(c->v_t.reserve(nb));
+    HSS_TRY(c->v_u.reserve(nb));
+    HSS_TRY(c->partial.reserve(sizeof(double) * (4 + 2 * MAX_NRHS) * VEC_BLOCKS));
     double* part = c->partial.as<double>();
     double* scal = c->scal.as<double>();
     double* w1 = scal + 4;
-    // w = Y K_beta^{-1} e,  w1 = e^T K_beta^{-1} e   (Algorithm 3, lines 4-6)
-    HSS_TRY(fill_launch(st, rhs, n, 1.0));
-    HSS_TRY(ulv_solve_perm(c, rhs, sol));
-    HSS_TRY(vec_dot(st, sol, nullptr, n, part, w1));
-    HSS_TRY(vec_mul(st, c->v_w.as<double>(), c->yp.as<double>(), sol, n));
-    AdmmVecs v{c->v_x.as<double>(), c->v_z.as<double>(), c->v_mu.as<double>(), rhs, sol, c->yp.as<double>(),
-               c->v_w.as<double>()};
-    double* pa = part + VEC_BLOCKS;
-    double* pb = part + 2 * VEC_BLOCKS;
-    HSS_TRY(admm_start(st, v, n, pa));
-    for (int it = 0; it < maxit; ++it) {
-        HSS_TRY(ulv_solve_perm(c, rhs, sol));
-        HSS_TRY(admm_step(st, v, n, C, beta, w1, pa, pb));
-        std::swap(pa, pb);
-    }
-    // bias over the margin set with one HSS mat-vec (eq. 7; sign from the margin condition)
-    double* ebar = c->v_e.as<double>();
-    HSS_TRY(margin_indicator(st, v.z, C, ebar, n));
-    HIP_TRY(hipMemcpyAsync(c->mv_x.p, ebar, nb, hipMemcpyDeviceToDevice, st));
-    HSS_TRY(hss_matvec_perm(c));
-    HSS_TRY(bias_sums(st, v.z, c->yp.as<double>(), c->mv_y.as<double>(), ebar, n, part, scal));
-    double sums[3];
-    HIP_TRY(hipMemcpyAsync(sums, scal, sizeof(sums), hipMemcpyDeviceToHost, st));
     const int64_t* perm = c->perm.as<int64_t>();
-    if (x_out) HSS_TRY(vec_scatter(st, x_out, v.x, perm, n));
-    if (z_out) HSS_TRY(vec_scatter(st, z_out, v.z, perm, n));
-    if (mu_out) HSS_TRY(vec_scatter(st, mu_out, v.mu, perm, n));
-    HIP_TRY(hipStreamSynchronize(st));
-    const int64_t cnt = (int64_t)(sums[2] + 0.5);
-    double b = 0.0;
-    if (cnt > 0) b = (sums[0] - sums[1]) / (double)cnt;
-    else warn |= HSS_WNOMARGIN;
-    if (bias_out) *bias_out = b;
-    if (n_margin_out) *n_margin_out = cnt;
+    // w = Y K_beta^{-1} e,  w1 = e^T K_beta^{-1} e: the same for every C (Algorithm 3, the lines before the loop)
+    HSS_TRY(fill_launch(st, solve_rhs(c), n, 1.0));
+    HSS_TRY(ulv_solve_inplace(c, 1));
+    HSS_TRY(vec_dot(st, solve_sol(c, 1), nullptr, n, part, w1));
+    HSS_TRY(vec_mul(st, c->v_w.as<double>(), c->yp.as<double>(), solve_sol(c, 1), n));
+    for (int j0 = 0; j0 < nC;) {
+        const int g = std::min(nC - j0, MAX_NRHS);
+        const int nr = g == 1 ? 1 : (g == 2 ? 2 : 4);     // three columns run as four, the last one twice
+        CBox box;
+        for (int j = 0; j < 4; ++j) box.c[j] = C_list[j0 + std::min(j, g - 1)];
+        AdmmVecs v{c->v_x.as<double>(), c->v_z.as<double>(), c->v_mu.as<double>(), solve_rhs(c), solve_sol(c, nr),
+                   c->yp.as<double>(), c->v_w.as<double>()};
+        double* pa = part + 4 * VEC_BLOCKS;
+        double* pb = pa + MAX_NRHS * VEC_BLOCKS;
+        HSS_TRY(admm_start(st, v, n, nr, pa));
+        for (int it = 0; it < maxit; ++it) {
+            HSS_TRY(ulv_solve_inplace(c, nr));
+            HSS_TRY(admm_step(st, v, n, nr, box, beta, w1, pa, pb));
+            std::swap(pa, pb);
+        }
+        // per column: bias over the margin set with one HSS mat-vec (eq. 7; sign from the margin condition)
+        for (int j = 0; j < g; ++j) {
+            double* zc = c->v_t.as<double>();
+            double* tmp = c->v_u.as<double>();
+            double* ebar = c->v_e.as<double>();
+            const double C = C_list[j0 + j];
+            HSS_TRY(vec_column(st, zc, v.z, n, nr, j));
+            HSS_TRY(margin_indicator(st, zc, C, ebar, n));
+            HIP_TRY(hipMemcpyAsync(c->mv_x.p, ebar, nb, hipMemcpyDeviceToDevice, st));
+            HSS_TRY(hss_matvec_perm(c));
+            HSS_TRY(bias_sums(st, zc, c->yp.as<double>(), c->mv_y.as<double>(), ebar, n, part, scal));
+            double sums[3];
+            HIP_TRY(hipMemcpyAsync(sums, scal, sizeof(sums), hipMemcpyDeviceToHost, st));
+            const size_t off = (size_t)(j0 + j) * n;
+            if (z_out) HSS_TRY(vec_scatter(st, z_out + off, zc, perm, n));
+            if (x_out) {
+                HSS_TRY(vec_column(st, tmp, v.x, n, nr, j));
+                HSS_TRY(vec_scatter(st, x_out + off, tmp, perm, n));
+            }
+            if (mu_out) {
+                HSS_TRY(vec_column(st, tmp, v.mu, n, nr, j));
+                HSS_TRY(vec_scatter(st, mu_out + off, tmp, perm, n));
+            }
+            HIP_TRY(hipStreamSynchronize(st));
+            const int64_t cnt = (int64_t)(sums[2] + 0.5);
+            double b = 0.0;
+            if (cnt > 0) b = (sums[0] - sums[1]) / (double)cnt;
+            else warn |= HSS_WNOMARGIN;
+            if (bias_out) bias_out[j0 + j] = b;
+            if (n_margin_out) n_margin_out[j0 + j] = cnt;
+        }
+        j0 += g;
+    }
     c->warnings |= warn;
     return warn;
+}
+
+int admm_svm_train(hss_ctx* c, double C, double beta, int32_t maxit, double* x_out, double* z_out, double* mu_out,
+                   double* bias_out, int64_t* n_margin_out) {
+    return admm_svm_train_multi(c, &C, 1, beta, maxit, x_out, z_out, mu_out, bias_out, n_margin_out);
 }
 
 int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, double bias, double* dec) {

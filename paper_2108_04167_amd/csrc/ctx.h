@@ -29,7 +29,8 @@ struct Level {
     std::vector<int64_t> kkoff;             // prefix sums of rk*rk
     DevBuf RT, RTi;                         // R^T and R^-T per node (k x k), R = reduced basis handed to the parent
     // solve plumbing
-    DevBuf bvec, ce, xvec;                  // level vectors: input (sum msz), eliminated part (sum msz-rk), output (sum msz)
+    double *bvec = nullptr, *ce = nullptr, *xvec = nullptr;   // level vectors inside hss_ctx::vpool (single-column
+                                            // layout): input (sum msz), eliminated part (sum msz-rk), output (sum msz)
     DevBuf up_items, down_items, work;      // SolveItem tables and the (node, row block) work list
     int nwork = 0;
     int rows_per_wave = 4;                  // launch shape of the level's solve kernel
@@ -57,6 +58,9 @@ struct hss_ctx {
     std::vector<int64_t> perm_host;
     std::vector<Level> lev;                 // 0 .. L
     DevBuf rootinv;                         // inverse of the root block (root_m x root_m)
+    DevBuf vpool;                           // all level vectors of the solve, MAX_NRHS x their single-column length:
+                                            // with nrhs interleaved right-hand sides a vector at pool + o lives at
+                                            // pool + o * nrhs
     int root_m = 0;
     DevBuf flags;                           // int[4] device flags (bit 0: tiny pivot)
     DescArena arena;
@@ -82,3 +86,11 @@ int hss_matvec_perm(hss_ctx* c);           // mv_y = K~' mv_x  (cluster-tree ord
 // ulv.hip
 int ulv_factor_impl(hss_ctx* c, double beta);
 int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm);   // cluster-tree order; may alias
+// nrhs in {1, 2, 4} interleaved right-hand sides, in place in the leaf-level vectors: input in
+// solve_rhs(c), result in solve_sol(c) (entry i of column j at [i * nrhs + j])
+int ulv_solve_inplace(hss_ctx* c, int nrhs);
+inline double* solve_rhs(hss_ctx* c) { return c->lev[c->L].bvec; }   // pool offset 0
+inline double* solve_sol(hss_ctx* c, int nrhs) {
+    return c->vpool.as<double>() + (c->lev[c->L].xvec - c->vpool.as<double>()) * nrhs;
+}
+constexpr int MAX_NRHS = 4;

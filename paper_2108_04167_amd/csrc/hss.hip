@@ -227,7 +227,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->arena.reset();
     HSS_TRY(c->flags.reserve(sizeof(int) * 4));
     HIP_TRY(hipMemsetAsync(c->flags.p, 0, sizeof(int) * 4, st));
-    HSS_TRY(c->partial.reserve(sizeof(double) * 4 * VEC_BLOCKS));
+    HSS_TRY(c->partial.reserve(sizeof(double) * (4 + 2 * MAX_NRHS) * VEC_BLOCKS));
     HSS_TRY(c->scal.reserve(sizeof(double) * 16));
 
     // ---- labels must be +-1 (checked on the host copy); cluster tree on the device ----
@@ -511,7 +511,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
     c->arena.reset();
     HSS_TRY(c->flags.reserve(sizeof(int) * 4));
     HIP_TRY(hipMemsetAsync(c->flags.p, 0, sizeof(int) * 4, st));
-    HSS_TRY(c->partial.reserve(sizeof(double) * 4 * VEC_BLOCKS));
+    HSS_TRY(c->partial.reserve(sizeof(double) * (4 + 2 * MAX_NRHS) * VEC_BLOCKS));
     HSS_TRY(c->scal.reserve(sizeof(double) * 16));
     std::vector<double> yh(n);
     HIP_TRY(hipMemcpyAsync(yh.data(), y, sizeof(double) * n, hipMemcpyDeviceToHost, st));

@@ -19,8 +19,10 @@ struct GemvItem {
     int32_t M, N, lda, pad;
 };
 
-// rows_per_wave in {1, 2, 4, 8}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node
+// rows_per_wave in {1, 2, 4, 8}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
+// nrhs in {1, 2, 4} interleaved right-hand sides; `pool` is the allocation all vector pointers of the item
+// tables point into (a pointer p of the tables stands for pool + (p - pool) * nrhs).
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
-                       bool vec);
+                       bool vec, int nrhs, double* pool);
 int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool trans, double alpha,
                  double beta);

@@ -22,31 +22,52 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-// One wavefront computes R consecutive rows of y = M x for one node; the input vector lives in registers
-// (lane l holds the columns it multiplies), so a wavefront issues its loads of x and of its R matrix rows
-// back to back and waits once.  VEC: 16-byte loads (needs even m, n0, ld and 16-byte aligned pointers).
+// One wavefront computes R consecutive rows of Y = M X for one node and NR right-hand sides; the input
+// vectors live in registers (lane l holds the columns it multiplies), so a wavefront issues its loads of X
+// and of its R matrix rows back to back and waits once, and every matrix entry is used NR times.
+// VEC: 16-byte loads (needs even m, n0, ld and 16-byte aligned pointers).
 // A workgroup = 4 wavefronts = 4R rows; the work list gives (node, first row).
-template <int R, bool VEC>
+//
+// Right-hand sides are interleaved: entry i of column j sits at v[i * NR + j].  The item tables hold the
+// pointers of the single-column layout, all inside one pool; for NR > 1 a pointer p stands for
+// pool + (p - pool) * NR.
+template <int NR>
+__device__ __forceinline__ const double* scaled(const double* p, const double* pool) {
+    return (NR == 1 || p == nullptr) ? p : pool + (p - pool) * NR;
+}
+template <int NR>
+__device__ __forceinline__ double* scaled(double* p, double* pool) {
+    return (NR == 1 || p == nullptr) ? p : pool + (p - pool) * NR;
+}
+
+template <int R, bool VEC, int NR>
 __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __restrict__ items,
-                                                         const int2* __restrict__ work) {
+                                                         const int2* __restrict__ work, double* pool) {
     const int2 w = work[blockIdx.x];
     const SolveItem it = items[w.x];
     const int m = it.m;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (it.M == nullptr) {   // nothing was eliminated at this node: hand the vector through
-        for (int r = w.y + tid; r < w.y + 4 * R && r < m; r += 256) {
-            double v = r < it.n0 ? it.in0[r] : it.in1[r - it.n0];
-            if (r < it.nout0) it.out0[r] = v;
-            else it.out1[r - it.nout0] = v;
+    const double* in0 = scaled<NR>(it.in0, pool);
+    const double* in1 = scaled<NR>(it.in1, pool);
+    double* out0 = scaled<NR>(it.out0, pool);
+    double* out1 = scaled<NR>(it.out1, pool);
+    if (it.M == nullptr) {   // nothing was eliminated at this node: hand the vectors through
+        const int lo = w.y * NR, hi = (w.y + 4 * R < m ? w.y + 4 * R : m) * NR;
+        for (int e = lo + tid; e < hi; e += 256) {
+            const double v = e < it.n0 * NR ? in0[e] : in1[e - it.n0 * NR];
+            if (e < it.nout0 * NR) out0[e] = v;
+            else out1[e - it.nout0 * NR] = v;
         }
         return;
     }
     const int row0 = w.y + wave * R;
     if (row0 >= m) return;
     constexpr int KMAX = 16;   // m <= 1024
-    double s[R];
+    double s[R][NR];
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) s[rr] = 0.0;
+    for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+        for (int j = 0; j < NR; ++j) s[rr][j] = 0.0;
     const double* rowp[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) rowp[rr] = it.M + (size_t)(row0 + rr < m ? row0 + rr : m - 1) * it.ld;
@@ -55,15 +76,25 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
         for (int k = 0; k < KMAX / 2; ++k) {
             const int c = 2 * lane + 128 * k;
             if (128 * k < m) {          // uniform
-                double2 xv = make_double2(0.0, 0.0);
-                if (c < m) xv = c < it.n0 ? *reinterpret_cast<const double2*>(it.in0 + c)
-                                          : *reinterpret_cast<const double2*>(it.in1 + (c - it.n0));
+                double x0[NR], x1[NR];
+#pragma unroll
+                for (int j = 0; j < NR; ++j) x0[j] = x1[j] = 0.0;
+                if (c < m) {            // c and n0 are even: both columns come from the same input
+                    const double* src = c < it.n0 ? in0 + (size_t)c * NR : in1 + (size_t)(c - it.n0) * NR;
+#pragma unroll
+                    for (int q = 0; q < NR; ++q) {      // 2 NR consecutive doubles, 16 bytes at a time
+                        const double2 t = *reinterpret_cast<const double2*>(src + 2 * q);
+                        if (2 * q < NR) x0[2 * q] = t.x; else x1[2 * q - NR] = t.x;
+                        if (2 * q + 1 < NR) x0[2 * q + 1] = t.y; else x1[2 * q + 1 - NR] = t.y;
+                    }
+                }
                 const int cc = c < m ? c : 0;
 #pragma unroll
                 for (int rr = 0; rr < R; ++rr) {
                     // streamed once per sweep: non-temporal, so the factors do not displace the vectors in cache
                     const v2d a = __builtin_nontemporal_load(reinterpret_cast<const v2d*>(rowp[rr] + cc));
-                    s[rr] += a.x * xv.x + a.y * xv.y;
+#pragma unroll
+                    for (int j = 0; j < NR; ++j) s[rr][j] += a.x * x0[j] + a.y * x1[j];
                 }
             }
         }
@@ -72,23 +103,36 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
         for (int k = 0; k < KMAX; ++k) {
             const int c = lane + 64 * k;
             if (64 * k < m) {           // uniform
-                double xv = 0.0;
-                if (c < m) xv = c < it.n0 ? it.in0[c] : it.in1[c - it.n0];
+                double xv[NR];
+#pragma unroll
+                for (int j = 0; j < NR; ++j) xv[j] = 0.0;
+                if (c < m) {
+                    const double* src = c < it.n0 ? in0 + (size_t)c * NR : in1 + (size_t)(c - it.n0) * NR;
+#pragma unroll
+                    for (int j = 0; j < NR; ++j) xv[j] = src[j];
+                }
                 const int cc = c < m ? c : 0;
 #pragma unroll
-                for (int rr = 0; rr < R; ++rr) s[rr] += __builtin_nontemporal_load(rowp[rr] + cc) * xv;
+                for (int rr = 0; rr < R; ++rr) {
+                    const double a = __builtin_nontemporal_load(rowp[rr] + cc);
+#pragma unroll
+                    for (int j = 0; j < NR; ++j) s[rr][j] += a * xv[j];
+                }
             }
         }
     }
 #pragma unroll
-    for (int rr = 0; rr < R; ++rr) s[rr] = wave_sum(s[rr]);
+    for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+        for (int j = 0; j < NR; ++j) s[rr][j] = wave_sum(s[rr][j]);
     if (lane == 0) {
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) {
             const int r = row0 + rr;
             if (r < m) {
-                if (r < it.nout0) it.out0[r] = s[rr];
-                else it.out1[r - it.nout0] = s[rr];
+                double* dst = r < it.nout0 ? out0 + (size_t)r * NR : out1 + (size_t)(r - it.nout0) * NR;
+#pragma unroll
+                for (int j = 0; j < NR; ++j) dst[j] = s[rr][j];
             }
         }
     }
@@ -143,14 +187,21 @@ __global__ __launch_bounds__(256) void bgemv_t_kernel(const GemvItem* __restrict
 }  // namespace
 
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
-                       bool vec) {
+                       bool vec, int nrhs, double* pool) {
     if (nwork <= 0) return HSS_OK;
     dim3 g((unsigned)nwork), b(256);
-#define HSS_SOLVE_CASE(R)                                                                                     \
-    case R:                                                                                                   \
-        if (vec) hipLaunchKernelGGL((solve_gemv_kernel<R, true>), g, b, 0, st, items_dev, work_dev);          \
-        else hipLaunchKernelGGL((solve_gemv_kernel<R, false>), g, b, 0, st, items_dev, work_dev);             \
+#define HSS_SOLVE_GO(R, NR)                                                                                       \
+    do {                                                                                                          \
+        if (vec) hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR>), g, b, 0, st, items_dev, work_dev, pool);    \
+        else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR>), g, b, 0, st, items_dev, work_dev, pool);       \
+    } while (0)
+#define HSS_SOLVE_CASE(R)                                                                                         \
+    case R:                                                                                                       \
+        if (nrhs == 1) HSS_SOLVE_GO(R, 1);                                                                        \
+        else if (nrhs == 2) HSS_SOLVE_GO(R, 2);                                                                   \
+        else HSS_SOLVE_GO(R, 4);                                                                                  \
         break;
+    if (nrhs != 1 && nrhs != 2 && nrhs != 4) return HSS_EINVAL;
     switch (rows_per_wave) {
         HSS_SOLVE_CASE(1)
         HSS_SOLVE_CASE(2)
@@ -159,6 +210,7 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
         default: return HSS_EINVAL;
     }
 #undef HSS_SOLVE_CASE
+#undef HSS_SOLVE_GO
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }

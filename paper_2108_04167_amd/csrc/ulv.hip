@@ -57,12 +57,29 @@ int invert_root(hss_ctx* c, double* D, int m, double tiny) {
 
 int build_solve_tables(hss_ctx* c) {
     const int L = c->L;
-    for (int l = 0; l <= L; ++l) {
-        Level& lv = c->lev[l];
-        const int64_t rows = lv.moff[lv.N];
-        HSS_TRY(lv.bvec.reserve(sizeof(double) * rows));
-        HSS_TRY(lv.xvec.reserve(sizeof(double) * rows));
-        HSS_TRY(lv.ce.reserve(sizeof(double) * std::max<int64_t>(rows - lv.koff[lv.N], 1)));
+    // every level vector is a slice of one pool (even offsets, the leaf input first)
+    {
+        int64_t total = 0;
+        auto take = [&](int64_t len) {
+            const int64_t o = total;
+            total += round_up(std::max<int64_t>(len, 2), 2);
+            return o;
+        };
+        std::vector<int64_t> ob(L + 1), ox(L + 1), oc(L + 1);
+        for (int l = L; l >= 0; --l) {
+            Level& lv = c->lev[l];
+            const int64_t rows = lv.moff[lv.N];
+            ob[l] = take(rows);
+            ox[l] = take(rows);
+            oc[l] = take(rows - lv.koff[lv.N]);
+        }
+        HSS_TRY(c->vpool.reserve(sizeof(double) * (size_t)total * MAX_NRHS));
+        double* pool = c->vpool.as<double>();
+        for (int l = 0; l <= L; ++l) {
+            c->lev[l].bvec = pool + ob[l];
+            c->lev[l].xvec = pool + ox[l];
+            c->lev[l].ce = pool + oc[l];
+        }
     }
     // When no leaf eliminates anything (rank == leaf size everywhere) the leaves' vectors ARE the vectors of
     // the level above (same layout), so that level works on them in place and the leaf level launches nothing.
@@ -73,8 +90,8 @@ int build_solve_tables(hss_ctx* c) {
     for (int l = L; l >= 0; --l) {
         Level& lv = c->lev[l];
         std::vector<SolveItem> up(lv.N), dn(lv.N);
-        double* my_bvec = (leaves_pass && l == L - 1) ? c->lev[L].bvec.as<double>() : lv.bvec.as<double>();
-        double* my_xvec = (leaves_pass && l == L - 1) ? c->lev[L].xvec.as<double>() : lv.xvec.as<double>();
+        double* my_bvec = (leaves_pass && l == L - 1) ? c->lev[L].bvec : lv.bvec;
+        double* my_xvec = (leaves_pass && l == L - 1) ? c->lev[L].xvec : lv.xvec;
         std::vector<int2> work;
         // launch shape: enough workgroups to fill the chip (4 x rows_per_wave rows each); 16-byte loads when
         // every size and offset of the level is even
@@ -98,9 +115,9 @@ int build_solve_tables(hss_ctx* c) {
                 Level& pl = c->lev[l - 1];
                 const double* Mu = lv.pass[t] ? nullptr : lv.Mup.as<double>() + lv.foff[t];
                 const double* Md = lv.pass[t] ? nullptr : lv.Mdown.as<double>() + lv.foff[t];
-                double* ce = lv.ce.as<double>() + (lv.moff[t] - lv.koff[t]);
-                up[t] = SolveItem{Mu, my_bvec + lv.moff[t], nullptr, pl.bvec.as<double>() + lv.koff[t], ce, m, m, m, k};
-                dn[t] = SolveItem{Md, pl.xvec.as<double>() + lv.koff[t], ce, my_xvec + lv.moff[t], nullptr, m, m, k, m};
+                double* ce = lv.ce + (lv.moff[t] - lv.koff[t]);
+                up[t] = SolveItem{Mu, my_bvec + lv.moff[t], nullptr, pl.bvec + lv.koff[t], ce, m, m, m, k};
+                dn[t] = SolveItem{Md, pl.xvec + lv.koff[t], ce, my_xvec + lv.moff[t], nullptr, m, m, k, m};
             }
             for (int r0 = 0; r0 < m; r0 += rb) work.push_back(make_int2(t, r0));
         }
@@ -412,28 +429,39 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
     return warn;
 }
 
-// x = (K~ + (delta + beta) I)^{-1} b in cluster-tree order.
-int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm) {
+// The sweeps of one solve for nrhs interleaved right-hand sides sitting in the leaf-level input vector.
+int ulv_solve_inplace(hss_ctx* c, int nrhs) {
     hipStream_t st = c->stream;
     const int L = c->L;
-    Level& ll = c->lev[L];
-    if (b_perm != ll.bvec.as<double>())
-        HIP_TRY(hipMemcpyAsync(ll.bvec.p, b_perm, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
+    double* pool = c->vpool.as<double>();
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
-        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec));
+        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec,
+                                   nrhs, pool));
     }
     {
         Level& rl = c->lev[0];
-        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.vec));
+        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.vec,
+                                   nrhs, pool));
     }
     for (int l = 1; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
-        HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec));
+        HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave,
+                                   lv.vec, nrhs, pool));
     }
-    if (x_perm != ll.xvec.as<double>())
-        HIP_TRY(hipMemcpyAsync(x_perm, ll.xvec.p, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
+    return HSS_OK;
+}
+
+// x = (K~ + (delta + beta) I)^{-1} b in cluster-tree order.
+int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm) {
+    hipStream_t st = c->stream;
+    Level& ll = c->lev[c->L];
+    if (b_perm != ll.bvec)
+        HIP_TRY(hipMemcpyAsync(ll.bvec, b_perm, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
+    HSS_TRY(ulv_solve_inplace(c, 1));
+    if (x_perm != ll.xvec)
+        HIP_TRY(hipMemcpyAsync(x_perm, ll.xvec, sizeof(double) * c->n, hipMemcpyDeviceToDevice, st));
     return HSS_OK;
 }

@@ -21,9 +21,16 @@ int vec_mul(hipStream_t st, double* dst, const double* a, const double* b, int64
 int vec_dot(hipStream_t st, const double* a, const double* b, int64_t n, double* partial_dev, double* out_dev);
 int vec_axpby(hipStream_t st, double* y, const double* x, double a, double b, int64_t n);
 int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, double alpha, double beta, int64_t n);
-int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, double* part_out);
-int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, double C, double beta, const double* w1_dev,
+struct CBox {
+    double c[4];        // box bound C of each interleaved column
+};
+// nr in {1, 2, 4} interleaved columns (x, z, mu, rhs, sol); partials: nr * vec_blocks(n) doubles
+int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, int nr, double* part_out);
+int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, int nr, const CBox& box, double beta, const double* w1_dev,
               const double* part_in, double* part_out);
+int vec_column(hipStream_t st, double* dst, const double* src, int64_t n, int nr, int j);
+int vec_gather_cols(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n, int nr, int ncols);
+int vec_scatter_cols(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n, int nr, int ncols);
 int margin_indicator(hipStream_t st, const double* z, double C, double* ebar, int64_t n);
 int bias_sums(hipStream_t st, const double* z, const double* y, const double* u, const double* ebar, int64_t n,
               double* partial_dev, double* out_dev);

@@ -66,48 +66,93 @@ __global__ void mul_kernel(double* __restrict__ dst, const double* __restrict__ 
     if (i < n) dst[i] = a[i] * b[i];
 }
 
+// The ADMM kernels run NR independent problems that differ only in the box bound C (one beta, one
+// factorization): x, z, mu, rhs and sol hold NR interleaved columns (entry i of column j at [i * NR + j]),
+// y and w are shared.  Partial sums of column j go to part[j * gridDim.x + workgroup].
+//
 // Start of a run: x = z = mu = 0, q = e, rhs = Y q = y, partial sums of w^T q.
+template <int NR>
 __global__ __launch_bounds__(256) void admm_start_kernel(AdmmVecs v, int64_t n, double* __restrict__ part_out) {
     __shared__ double sh[4];
     double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        v.x[i] = 0.0;
-        v.z[i] = 0.0;
-        v.mu[i] = 0.0;
-        v.rhs[i] = v.y[i];
+        const double yi = v.y[i];
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            v.x[i * NR + j] = 0.0;
+            v.z[i * NR + j] = 0.0;
+            v.mu[i * NR + j] = 0.0;
+            v.rhs[i * NR + j] = yi;
+        }
         acc += v.w[i];
     }
     acc = block_sum(acc, sh);
-    if (threadIdx.x == 0) part_out[blockIdx.x] = acc;
+    if (threadIdx.x == 0)
+        for (int j = 0; j < NR; ++j) part_out[(size_t)j * gridDim.x + blockIdx.x] = acc;
 }
 
 // One iteration after the solve: sol holds K_beta^{-1} Y q^k.
 //   x = Y sol - (w2 / w1) w;  z = clip(x - mu/beta, 0, C);  mu -= beta (x - z);
 //   q = e + mu + beta z;  rhs = Y q;  partial sums of w^T q for the next iteration.
-__global__ __launch_bounds__(256) void admm_step_kernel(AdmmVecs v, int64_t n, double C, double beta,
+template <int NR>
+__global__ __launch_bounds__(256) void admm_step_kernel(AdmmVecs v, int64_t n, CBox box, double beta,
                                                         const double* __restrict__ w1, const double* __restrict__ part_in,
                                                         int nparts, double* __restrict__ part_out) {
     __shared__ double sh[4];
-    const double w2 = sum_partials(part_in, nparts, sh);
-    const double ratio = w2 / (*w1);
+    double ratio[NR], acc[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const double w2 = sum_partials(part_in + (size_t)j * nparts, nparts, sh);
+        ratio[j] = w2 / (*w1);
+        acc[j] = 0.0;
+    }
     const double ibeta = 1.0 / beta;
-    double acc = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
         const double yi = v.y[i], wi = v.w[i];
-        const double mu = v.mu[i];
-        const double x = yi * v.sol[i] - ratio * wi;
-        double z = x - mu * ibeta;
-        z = z < 0.0 ? 0.0 : (z > C ? C : z);
-        const double mun = mu - beta * (x - z);
-        v.x[i] = x;
-        v.z[i] = z;
-        v.mu[i] = mun;
-        const double q = 1.0 + mun + beta * z;
-        v.rhs[i] = yi * q;
-        acc += wi * q;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int64_t e = i * NR + j;
+            const double C = box.c[j];
+            const double mu = v.mu[e];
+            const double x = yi * v.sol[e] - ratio[j] * wi;
+            double z = x - mu * ibeta;
+            z = z < 0.0 ? 0.0 : (z > C ? C : z);
+            const double mun = mu - beta * (x - z);
+            v.x[e] = x;
+            v.z[e] = z;
+            v.mu[e] = mun;
+            const double q = 1.0 + mun + beta * z;
+            v.rhs[e] = yi * q;
+            acc[j] += wi * q;
+        }
     }
-    acc = block_sum(acc, sh);
-    if (threadIdx.x == 0) part_out[blockIdx.x] = acc;
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const double a = block_sum(acc[j], sh);
+        if (threadIdx.x == 0) part_out[(size_t)j * gridDim.x + blockIdx.x] = a;
+    }
+}
+
+// dst[i] = src[i * nr + j]: one column out of an interleaved block
+__global__ void column_kernel(double* __restrict__ dst, const double* __restrict__ src, int64_t n, int nr, int j) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[i * nr + j];
+}
+// dst[i * nr + j] = src[j * n + perm[i]] for j < ncols (0 beyond): columns in caller order -> interleaved,
+// cluster-tree order; and back
+__global__ void gather_cols_kernel(double* __restrict__ dst, const double* __restrict__ src,
+                                   const int64_t* __restrict__ perm, int64_t n, int nr, int ncols) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t p = perm[i];
+    for (int j = 0; j < nr; ++j) dst[i * nr + j] = j < ncols ? src[(size_t)j * n + p] : 0.0;
+}
+__global__ void scatter_cols_kernel(double* __restrict__ dst, const double* __restrict__ src,
+                                    const int64_t* __restrict__ perm, int64_t n, int nr, int ncols) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t p = perm[i];
+    for (int j = 0; j < ncols; ++j) dst[(size_t)j * n + p] = src[i * nr + j];
 }
 
 // ebar_i = 1 if 0 < z_i < C else 0
@@ -245,15 +290,38 @@ int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double*
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
-int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, double* part_out) {
-    hipLaunchKernelGGL(admm_start_kernel, dim3(vec_blocks(n)), dim3(256), 0, st, v, n, part_out);
+int admm_start(hipStream_t st, const AdmmVecs& v, int64_t n, int nr, double* part_out) {
+    const dim3 g(vec_blocks(n)), b(256);
+    if (nr == 1) hipLaunchKernelGGL(admm_start_kernel<1>, g, b, 0, st, v, n, part_out);
+    else if (nr == 2) hipLaunchKernelGGL(admm_start_kernel<2>, g, b, 0, st, v, n, part_out);
+    else if (nr == 4) hipLaunchKernelGGL(admm_start_kernel<4>, g, b, 0, st, v, n, part_out);
+    else return HSS_EINVAL;
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
-int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, double C, double beta, const double* w1_dev,
+int admm_step(hipStream_t st, const AdmmVecs& v, int64_t n, int nr, const CBox& box, double beta, const double* w1_dev,
               const double* part_in, double* part_out) {
     const int nb = vec_blocks(n);
-    hipLaunchKernelGGL(admm_step_kernel, dim3(nb), dim3(256), 0, st, v, n, C, beta, w1_dev, part_in, nb, part_out);
+    const dim3 g(nb), b(256);
+    if (nr == 1) hipLaunchKernelGGL(admm_step_kernel<1>, g, b, 0, st, v, n, box, beta, w1_dev, part_in, nb, part_out);
+    else if (nr == 2) hipLaunchKernelGGL(admm_step_kernel<2>, g, b, 0, st, v, n, box, beta, w1_dev, part_in, nb, part_out);
+    else if (nr == 4) hipLaunchKernelGGL(admm_step_kernel<4>, g, b, 0, st, v, n, box, beta, w1_dev, part_in, nb, part_out);
+    else return HSS_EINVAL;
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_column(hipStream_t st, double* dst, const double* src, int64_t n, int nr, int j) {
+    hipLaunchKernelGGL(column_kernel, dim3(eb(n)), dim3(256), 0, st, dst, src, n, nr, j);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_gather_cols(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n, int nr, int ncols) {
+    hipLaunchKernelGGL(gather_cols_kernel, dim3(eb(n)), dim3(256), 0, st, dst, src, perm, n, nr, ncols);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int vec_scatter_cols(hipStream_t st, double* dst, const double* src, const int64_t* perm, int64_t n, int nr, int ncols) {
+    hipLaunchKernelGGL(scatter_cols_kernel, dim3(eb(n)), dim3(256), 0, st, dst, src, perm, n, nr, ncols);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
