@@ -52,6 +52,50 @@ def cpu_baseline(cfg, n_small, maxit):
     return {"n": n_small, "t_sampling": t2 - t1, "t_rest": (t1 - t0) + (t3 - t2), "threads": threads}
 
 
+def sweep(args, w, ctx, F, y):
+    """The hyper-parameter grid of a workload (Sec. 3.2: compress once per h, factor once per beta, one ADMM run
+    per (C, beta)): lockstep C runs against the same grid as separate runs."""
+    import torch
+    Cs = list(w.C_grid) if w.C_grid else [w.C]
+    betas = list(w.beta_grid) if w.beta_grid else [w.beta]
+
+    def timed(f):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = f()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, out
+
+    t_compress, _ = timed(lambda: ctx.hss_compress(F, y, w.h, w.leaf, w.tol))
+    rows = []
+    t_factor = t_lock = t_sep = 0.0
+    for beta in betas:
+        tf, _ = timed(lambda: ctx.hss_ulv_factor(beta))
+        tl, multi = timed(lambda: ctx.admm_svm_train_multi(Cs, beta, w.maxit))
+        ts = 0.0
+        for j, Cj in enumerate(Cs):
+            t1, single = timed(lambda: ctx.admm_svm_train(Cj, beta, w.maxit))
+            ts += t1
+            dz = float((multi["z"][j] - single["z"]).abs().max().item())
+            rows.append({"C": Cj, "beta": beta, "bias": multi["bias"][j], "n_margin": multi["n_margin"][j],
+                         "max_abs_diff_z_vs_separate_run": dz})
+        t_factor += tf
+        t_lock += tl
+        t_sep += ts
+    st = ctx.hss_stats()
+    npairs = len(Cs) * len(betas)
+    rec = {"metric": "admm_hss_sweep_seconds", "value": t_compress + t_factor + t_lock, "unit": "s", "n_gpus": 1,
+           "higher_is_better": False, "dtype": "f64", "data": "synthetic",
+           "config": {"workload": f"cfg{args.cfg}" + (f" cut to n={w.n}" if args.n else ""), "n": w.n, "r": w.r,
+                      "h": w.h, "leaf": w.leaf, "sample_width": w.s, "C_grid": Cs, "beta_grid": betas,
+                      "admm_iterations": w.maxit},
+           "phases_s": {"compress": t_compress, "factor_all_betas": t_factor, "admm_lockstep_all_pairs": t_lock,
+                        "admm_separate_runs_all_pairs": t_sep},
+           "seconds_per_pair_lockstep": t_lock / npairs, "seconds_per_pair_separate": t_sep / npairs,
+           "solve_bytes": st["factor_bytes"], "pairs": rows}
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +106,9 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="also run one plain device-to-device copy of this many bytes (reference for HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the workload's C x beta grid instead (one compression, one factorization per beta, "
+                         "the C values of a beta in lockstep); prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding).", file=sys.stderr)
@@ -85,6 +132,9 @@ def main():
     y = torch.tensor(w.y, device=dev)
     ctx = binding.Context()
     ctx.hss_set_i64("sample_width", w.s)
+    if args.sweep:
+        sweep(args, w, ctx, F, y)
+        return
 
     def step():
         ctx.hss_compress(F, y, w.h, w.leaf, w.tol)                 # draws Omega in-library
