@@ -111,7 +111,7 @@ def main():
                          "the C values of a beta in lockstep); prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding).", file=sys.stderr)
+        print("bench.py: the library runs on ONE GPU; --gpus must be 1 (no collectives, no sharding).", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -38,6 +38,9 @@ struct Level {
     bool skip = false;                      // leaf level where no node eliminates anything: the level above reads
                                             // and writes the leaf vectors directly and no kernel is launched
     // mat-vec plumbing
+    DevBuf UT;                              // U^T (rk x msz) per node at uoff, nodes with rk < msz only
+    DevBuf BT;                              // B^T (k_b x k_a) per inner node at boff
+    bool mv_vec = false;                    // 16-byte loads allowed in this level's mat-vec tables
     DevBuf xt, g;                           // (sum rk) each
     DevBuf mv_up, mv_dn_u, mv_dn_b, mv_dn_bt, mv_leaf_d;   // GemvItem tables
     int n_dn_b = 0;

@@ -65,17 +65,51 @@ int build_matvec_tables(hss_ctx* c) {
         HSS_TRY(lv.xt.reserve(sizeof(double) * std::max<int64_t>(lv.koff[lv.N], 1)));
         HSS_TRY(lv.g.reserve(sizeof(double) * std::max<int64_t>(lv.koff[lv.N], 1)));
     }
+    // transposed copies of the generators, so that every product of the mat-vec streams matrix rows
+    c->arena.reset();
+    for (int l = 1; l <= L; ++l) {
+        Level& lv = c->lev[l];
+        Level& pl = c->lev[l - 1];
+        HSS_TRY(lv.UT.reserve(sizeof(double) * std::max<int64_t>(lv.uoff[lv.N], 1)));
+        HSS_TRY(pl.BT.reserve(sizeof(double) * std::max<int64_t>(pl.boff[pl.N], 1)));
+        std::vector<CopyItem> ci;
+        for (int t = 0; t < lv.N; ++t) {
+            const int m = lv.msz[t], k = lv.rk[t];
+            if (k < m)
+                ci.push_back(CopyItem{lv.U.as<double>() + lv.uoff[t], lv.UT.as<double>() + lv.uoff[t], k, m, k, m, COPY_TRANS,
+                                      0, 0.0});
+        }
+        for (int i = 0; i < pl.N; ++i) {
+            const int ka = lv.rk[2 * i], kb = lv.rk[2 * i + 1];
+            ci.push_back(CopyItem{pl.B.as<double>() + pl.boff[i], pl.BT.as<double>() + pl.boff[i], kb, ka, kb, ka, COPY_TRANS,
+                                  0, 0.0});
+        }
+        HSS_TRY(bcopy(st, c->arena, ci));
+    }
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
         const double* xin = (l == L) ? mvx : c->lev[l + 1].xt.as<double>();
         std::vector<GemvItem> up(lv.N), dn(lv.N);
+        bool even = true;
         for (int t = 0; t < lv.N; ++t) {
             const double* U = lv.U.as<double>() + lv.uoff[t];
-            up[t] = GemvItem{U, xin + lv.moff[t], lv.xt.as<double>() + lv.koff[t], lv.msz[t], lv.rk[t], lv.rk[t], 0};
+            const double* UT = lv.UT.as<double>() + lv.uoff[t];
+            const int32_t* J = lv.J.as<int32_t>() + lv.koff[t];
+            const int m = lv.msz[t], k = lv.rk[t];
+            if ((m | k) & 1) even = false;
+            double* xt = lv.xt.as<double>() + lv.koff[t];
+            const double* g = lv.g.as<double>() + lv.koff[t];
             // down: (node's rows) = U_t g_t, written where the children's g live (leaf: added to y)
             double* dst = (l == L) ? mvy + lv.moff[t] : c->lev[l + 1].g.as<double>() + lv.moff[t];
-            dn[t] = GemvItem{U, lv.g.as<double>() + lv.koff[t], dst, lv.msz[t], lv.rk[t], lv.rk[t], 0};
+            if (k == m) {   // the node kept all its rows: U_t is the permutation with U(J_j, j) = 1
+                up[t] = GemvItem{nullptr, xin + lv.moff[t], xt, J, k, m, m, GEMV_GATHER};
+                dn[t] = GemvItem{nullptr, g, dst, J, m, k, k, GEMV_SCATTER};
+            } else {
+                up[t] = GemvItem{UT, xin + lv.moff[t], xt, nullptr, k, m, m, GEMV_DENSE};
+                dn[t] = GemvItem{U, g, dst, nullptr, m, k, k, GEMV_DENSE};
+            }
         }
+        lv.mv_vec = even;
         HSS_TRY(upload(c, lv.mv_up, up));
         HSS_TRY(upload(c, lv.mv_dn_u, dn));
         // coupling through the parent's B: g_a (+)= B xt_b, g_b (+)= B^T xt_a
@@ -84,8 +118,11 @@ int build_matvec_tables(hss_ctx* c) {
         for (int i = 0; i < pl.N; ++i) {
             const int a = 2 * i, b = 2 * i + 1;
             const double* B = pl.B.as<double>() + pl.boff[i];
-            b1[i] = GemvItem{B, lv.xt.as<double>() + lv.koff[b], lv.g.as<double>() + lv.koff[a], lv.rk[a], lv.rk[b], lv.rk[b], 0};
-            b2[i] = GemvItem{B, lv.xt.as<double>() + lv.koff[a], lv.g.as<double>() + lv.koff[b], lv.rk[a], lv.rk[b], lv.rk[b], 0};
+            const double* BT = pl.BT.as<double>() + pl.boff[i];
+            b1[i] = GemvItem{B, lv.xt.as<double>() + lv.koff[b], lv.g.as<double>() + lv.koff[a], nullptr, lv.rk[a], lv.rk[b],
+                             lv.rk[b], GEMV_DENSE};
+            b2[i] = GemvItem{BT, lv.xt.as<double>() + lv.koff[a], lv.g.as<double>() + lv.koff[b], nullptr, lv.rk[b], lv.rk[a],
+                             lv.rk[a], GEMV_DENSE};
         }
         HSS_TRY(upload(c, lv.mv_dn_b, b1));
         HSS_TRY(upload(c, lv.mv_dn_bt, b2));
@@ -95,9 +132,10 @@ int build_matvec_tables(hss_ctx* c) {
     std::vector<GemvItem> dd(leafl.N);
     for (int t = 0; t < leafl.N; ++t)
         dd[t] = GemvItem{c->Dleaf.as<double>() + (size_t)t * c->leaf * c->leaf, mvx + (size_t)t * c->leaf,
-                         mvy + (size_t)t * c->leaf, c->leaf, c->leaf, c->leaf, 0};
+                         mvy + (size_t)t * c->leaf, nullptr, c->leaf, c->leaf, c->leaf, GEMV_DENSE};
     HSS_TRY(upload(c, leafl.mv_leaf_d, dd));
     HIP_TRY(hipStreamSynchronize(st));   // the host vectors above go out of scope
+    c->arena.reset();
     return HSS_OK;
 }
 
@@ -111,19 +149,19 @@ int hss_matvec_perm(hss_ctx* c) {
     double* mvy = c->mv_y.as<double>();
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
-        HSS_TRY(bgemv_launch(st, lv.mv_up.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, true, 1.0, 0.0));
+        HSS_TRY(bgemv_launch(st, lv.mv_up.as<GemvItem>(), lv.N, lv.maxk, lv.maxm, lv.mv_vec, 1.0, 0.0));
     }
     for (int l = 1; l <= L; ++l) {
         Level& lv = c->lev[l];
         // contribution handed down by the parent level (written by the parent's U g), then the coupling
         const double beta = (l == 1) ? 0.0 : 1.0;
-        HSS_TRY(bgemv_launch(st, lv.mv_dn_b.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, false, 1.0, beta));
-        HSS_TRY(bgemv_launch(st, lv.mv_dn_bt.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, true, 1.0, beta));
-        if (l < L) HSS_TRY(bgemv_launch(st, lv.mv_dn_u.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, false, 1.0, 0.0));
+        HSS_TRY(bgemv_launch(st, lv.mv_dn_b.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, lv.mv_vec, 1.0, beta));
+        HSS_TRY(bgemv_launch(st, lv.mv_dn_bt.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, lv.mv_vec, 1.0, beta));
+        if (l < L) HSS_TRY(bgemv_launch(st, lv.mv_dn_u.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, lv.mv_vec, 1.0, 0.0));
     }
     Level& leafl = c->lev[L];
-    HSS_TRY(bgemv_launch(st, leafl.mv_leaf_d.as<GemvItem>(), leafl.N, c->leaf, c->leaf, false, 1.0, 0.0));
-    if (L >= 1) HSS_TRY(bgemv_launch(st, leafl.mv_dn_u.as<GemvItem>(), leafl.N, leafl.maxm, leafl.maxk, false, 1.0, 1.0));
+    HSS_TRY(bgemv_launch(st, leafl.mv_leaf_d.as<GemvItem>(), leafl.N, c->leaf, c->leaf, true, 1.0, 0.0));
+    if (L >= 1) HSS_TRY(bgemv_launch(st, leafl.mv_dn_u.as<GemvItem>(), leafl.N, leafl.maxm, leafl.maxk, leafl.mv_vec, 1.0, 1.0));
     if (c->delta != 0.0) HSS_TRY(vec_axpby(st, mvy, mvx, c->delta, 1.0, c->n));
     return HSS_OK;
 }
@@ -131,7 +169,8 @@ int hss_matvec_perm(hss_ctx* c) {
 namespace {
 
 // delta = 1.1 * max(0, -lambda_min(K~)) from a Lanczos run on the HSS mat-vec (no re-orthogonalisation:
-// only the extreme Ritz value is used).
+// only the extreme Ritz value is used).  The run stops when the smallest Ritz value has moved by less than
+// 1e-3 (relative) over the last four steps, or after 64 steps.
 int definiteness_guard(hss_ctx* c) {
     hipStream_t st = c->stream;
     const int64_t n = c->n;
@@ -159,7 +198,7 @@ int definiteness_guard(hss_ctx* c) {
     double* part = c->partial.as<double>();
     double* scal = c->scal.as<double>();
     double* w = c->mv_y.as<double>();
-    std::vector<double> alpha, beta;
+    std::vector<double> alpha, beta, ritz;
     double bprev = 0.0;
     for (int j = 0; j < iters; ++j) {
         HIP_TRY(hipMemcpyAsync(c->mv_x.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
@@ -176,6 +215,8 @@ int definiteness_guard(hss_ctx* c) {
         HIP_TRY(hipStreamSynchronize(st));
         const double b = std::sqrt(b2 > 0.0 ? b2 : 0.0);
         if (!(b > 1e-12 * std::max(1.0, std::fabs(a))) || j + 1 == iters) break;
+        ritz.push_back(tridiag_min_eig(alpha, beta));
+        if (j >= 11 && std::fabs(ritz[j] - ritz[j - 4]) <= 1e-3 * std::fabs(ritz[j])) break;
         beta.push_back(b);
         // vprev <- vcur, vcur <- w / b
         HIP_TRY(hipMemcpyAsync(vprev.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));

@@ -12,11 +12,13 @@ struct SolveItem {           // y = M [in0(0:n0); in1(0:m-n0)];  y(0:nout0) -> o
     int32_t m, ld, n0, nout0;
 };
 
-struct GemvItem {
-    const double* A;         // M x N row-major
+enum { GEMV_DENSE = 0, GEMV_GATHER = 1, GEMV_SCATTER = 2 };
+struct GemvItem {            // y = alpha * op x + beta * y
+    const double* A;         // GEMV_DENSE: M x N row-major, y(0:M) = A x(0:N)
     const double* x;
     double*       y;
-    int32_t M, N, lda, pad;
+    const int32_t* perm;     // GEMV_GATHER: y[j] = x[perm[j]];  GEMV_SCATTER: y[perm[j]] = x[j]   (j < M)
+    int32_t M, N, lda, mode;
 };
 
 // rows_per_wave in {1, 2, 4, 8}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
@@ -24,5 +26,6 @@ struct GemvItem {
 // tables point into (a pointer p of the tables stands for pool + (p - pool) * nrhs).
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
                        bool vec, int nrhs, double* pool);
-int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool trans, double alpha,
+// vec: every M, N, lda of the table is even and every pointer 16-byte aligned
+int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool vec, double alpha,
                  double beta);

@@ -138,49 +138,63 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
     }
 }
 
-// y = alpha * A x + beta * y, A is M x N row-major; one wavefront per 4 rows.
-__global__ __launch_bounds__(256) void bgemv_n_kernel(const GemvItem* __restrict__ items, double alpha, double beta) {
+// Batched y = alpha * A x + beta * y for the HSS mat-vec, A (M x N, N <= 1024) row-major: a wavefront computes
+// four consecutive rows with the input vector in registers, as in the solve kernel; transposed products use a
+// transposed copy of the generator, so every product streams rows.  Items whose generator is a permutation
+// (a node that kept all its rows) only move entries.
+template <bool VEC>
+__global__ __launch_bounds__(256) void bgemv_rows_kernel(const GemvItem* __restrict__ items, double alpha, double beta) {
     const GemvItem it = items[blockIdx.x];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = (blockIdx.y * 4 + wave) * 4; r < it.M; r += gridDim.y * 16) {
-        double s[4] = {0.0, 0.0, 0.0, 0.0};
-        const double* a[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = it.A + (size_t)(r + u < it.M ? r + u : it.M - 1) * it.lda;
-        for (int c = lane; c < it.N; c += 64) {
-            const double xv = it.x[c];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s[u] += a[u][c] * xv;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (it.mode != GEMV_DENSE) {
+        for (int j = blockIdx.y * 256 + tid; j < it.M; j += gridDim.y * 256) {
+            const double v = alpha * (it.mode == GEMV_GATHER ? it.x[it.perm[j]] : it.x[j]);
+            double* dst = it.mode == GEMV_GATHER ? it.y + j : it.y + it.perm[j];
+            *dst = beta != 0.0 ? v + beta * (*dst) : v;
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) s[u] = wave_sum(s[u]);
-        if (lane < 4 && r + lane < it.M) {
-            double v = alpha * (lane == 0 ? s[0] : lane == 1 ? s[1] : lane == 2 ? s[2] : s[3]);
-            double* y = it.y + r + lane;
-            *y = beta != 0.0 ? v + beta * (*y) : v;
-        }
+        return;
     }
-}
-
-// y = alpha * A^T x + beta * y, A is M x N row-major; one workgroup per 64 columns, the four wavefronts
-// split the rows and are combined through LDS in a fixed order.
-__global__ __launch_bounds__(256) void bgemv_t_kernel(const GemvItem* __restrict__ items, double alpha, double beta) {
-    const GemvItem it = items[blockIdx.x];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __shared__ double part[4][64];
-    for (int c0 = blockIdx.y * 64; c0 < it.N; c0 += gridDim.y * 64) {
-        const int c = c0 + lane;
-        double s = 0.0;
-        if (c < it.N)
-            for (int r = wave; r < it.M; r += 4) s += it.A[(size_t)r * it.lda + c] * it.x[r];
-        part[wave][lane] = s;
-        __syncthreads();
-        if (wave == 0 && c < it.N) {
-            double v = alpha * (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]);
-            double* y = it.y + c;
+    constexpr int R = 4, KMAX = 16;
+    const int N = it.N;
+    for (int row0 = (blockIdx.y * 4 + wave) * R; row0 < it.M; row0 += gridDim.y * 4 * R) {
+        double s[R] = {0.0, 0.0, 0.0, 0.0};
+        const double* rowp[R];
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) rowp[rr] = it.A + (size_t)(row0 + rr < it.M ? row0 + rr : it.M - 1) * it.lda;
+        if (VEC) {
+#pragma unroll
+            for (int k = 0; k < KMAX / 2; ++k) {
+                const int c = 2 * lane + 128 * k;
+                if (128 * k < N) {          // uniform
+                    double2 xv = make_double2(0.0, 0.0);
+                    if (c < N) xv = *reinterpret_cast<const double2*>(it.x + c);
+                    const int cc = c < N ? c : 0;
+#pragma unroll
+                    for (int rr = 0; rr < R; ++rr) {
+                        const v2d a = *reinterpret_cast<const v2d*>(rowp[rr] + cc);
+                        s[rr] += a.x * xv.x + a.y * xv.y;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                const int c = lane + 64 * k;
+                if (64 * k < N) {           // uniform
+                    const double xv = c < N ? it.x[c] : 0.0;
+                    const int cc = c < N ? c : 0;
+#pragma unroll
+                    for (int rr = 0; rr < R; ++rr) s[rr] += rowp[rr][cc] * xv;
+                }
+            }
+        }
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) s[rr] = wave_sum(s[rr]);
+        if (lane < R && row0 + lane < it.M) {
+            const double v = alpha * (lane == 0 ? s[0] : lane == 1 ? s[1] : lane == 2 ? s[2] : s[3]);
+            double* y = it.y + row0 + lane;
             *y = beta != 0.0 ? v + beta * (*y) : v;
         }
-        __syncthreads();
     }
 }
 
@@ -215,16 +229,17 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
     return HSS_OK;
 }
 
-int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool trans, double alpha,
+int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool vec, double alpha,
                  double beta) {
-    if (nitems <= 0 || maxM <= 0 || maxN <= 0) return HSS_OK;
-    if (!trans) {
-        unsigned yc = (unsigned)std::min(64, (maxM + 15) / 16);
-        hipLaunchKernelGGL(bgemv_n_kernel, dim3((unsigned)nitems, yc), dim3(256), 0, st, items_dev, alpha, beta);
-    } else {
-        unsigned yc = (unsigned)std::min(64, (maxN + 63) / 64);
-        hipLaunchKernelGGL(bgemv_t_kernel, dim3((unsigned)nitems, yc), dim3(256), 0, st, items_dev, alpha, beta);
-    }
+    if (nitems <= 0 || maxM <= 0) return HSS_OK;
+    if (maxN > 1024) return HSS_EUNSUPPORTED;
+    // enough workgroups to fill the chip, at most one per 16 rows
+    int yc = (maxM + 15) / 16;
+    while (yc > 1 && (int64_t)nitems * yc > 16384) yc = (yc + 1) / 2;
+    if (vec) hipLaunchKernelGGL(bgemv_rows_kernel<true>, dim3((unsigned)nitems, (unsigned)yc), dim3(256), 0, st, items_dev,
+                                alpha, beta);
+    else hipLaunchKernelGGL(bgemv_rows_kernel<false>, dim3((unsigned)nitems, (unsigned)yc), dim3(256), 0, st, items_dev,
+                            alpha, beta);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
