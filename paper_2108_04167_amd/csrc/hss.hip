@@ -342,13 +342,16 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
         if (L >= 1) HSS_TRY(bgemm_host(st, c->arena, gm, false, false, -1.0, 1.0));
     }
+    // The Gram form of the interpolative decomposition resolves pivots down to about 1e-7 of the largest one;
+    // it is used when the relative stop threshold stays well above that, the Gram-Schmidt form otherwise.
+    const bool gram_id = tol / 10.0 >= 3e-6;
     if (L >= 1) {
         HSS_TRY(S1.reserve(nsbytes));
         HSS_TRY(Om1.reserve(nsbytes));
-        HSS_TRY(Wk.reserve(nsbytes));
+        if (!gram_id) HSS_TRY(Wk.reserve(nsbytes));
     }
     const int kc = (int)kcap;
-    DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, rowmap;
+    DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, rowmap, Gm, d_goff;
     if (L >= 1) {
         HSS_TRY(Lc.reserve(sizeof(double) * (size_t)n * kc));
         HSS_TRY(norms0.reserve(sizeof(double) * n));
@@ -370,15 +373,31 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         const int N = lv.N;
         const int64_t rows = lv.moff[N];
         HSS_TRY(upload(c, lv.d_moff, lv.moff));
-        // interpolative decompositions of all nodes of the level, on a work copy of the sample rows
-        HIP_TRY(hipMemcpyAsync(Wk.p, Acur, sizeof(double) * (size_t)rows * s_pad, hipMemcpyDeviceToDevice, st));
+        // interpolative decompositions of all nodes of the level
         IdLevelArgs ia;
         ia.W = Wk.as<double>(); ia.ld = s_pad; ia.moff = lv.d_moff.as<int64_t>(); ia.kcap = (int)kcap; ia.kc = kc;
         ia.rows_per_block = 32; ia.rel = tol / 10.0; ia.abs_tol = c->opt_abs_tol;
         ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>(); ia.rk = rkd.as<int>();
         ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>();
-        HSS_TRY(id_init(st, ia, rows, N, norms0.as<double>()));
-        HSS_TRY(id_steps(st, ia, N, lv.maxm, norms0.as<double>(), norms1.as<double>()));
+        if (gram_id) {
+            // pivoted Cholesky of the nodes' Gram matrices S_t S_t^T (one workgroup per node, all steps in one launch)
+            std::vector<int64_t> goff(N + 1, 0);
+            for (int t = 0; t < N; ++t) goff[t + 1] = goff[t] + (int64_t)lv.msz[t] * lv.msz[t];
+            HSS_TRY(Gm.reserve(sizeof(double) * goff[N]));
+            HSS_TRY(upload(c, d_goff, goff));
+            std::vector<GemmItem> gg(N);
+            for (int t = 0; t < N; ++t) {
+                const double* St = Acur + (size_t)lv.moff[t] * s_pad;
+                gg[t] = GemmItem{St, St, Gm.as<double>() + goff[t], lv.msz[t], lv.msz[t], s_pad, s_pad, s_pad, lv.msz[t]};
+            }
+            HSS_TRY(bgemm_host(st, c->arena, gg, false, true, 1.0, 0.0));
+            HSS_TRY(id_chol(st, ia, N, lv.maxm, Gm.as<double>(), d_goff.as<int64_t>()));
+        } else {
+            // row-pivoted Gram-Schmidt on a work copy of the sample rows, one launch per pivot step
+            HIP_TRY(hipMemcpyAsync(Wk.p, Acur, sizeof(double) * (size_t)rows * s_pad, hipMemcpyDeviceToDevice, st));
+            HSS_TRY(id_init(st, ia, rows, N, norms0.as<double>()));
+            HSS_TRY(id_steps(st, ia, N, lv.maxm, norms0.as<double>(), norms1.as<double>()));
+        }
         lv.rk.resize(N);
         HIP_TRY(hipMemcpyAsync(lv.rk.data(), rkd.p, sizeof(int) * N, hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));

@@ -22,3 +22,4 @@ int id_init(hipStream_t st, const IdLevelArgs& a, int64_t nrows, int nnodes, dou
 int id_steps(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* norms0, double* norms1);
 int id_finish(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, const int64_t* koff, const int64_t* uoff,
               double* U, int* J);
+int id_chol(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* G, const int64_t* goff_dev);

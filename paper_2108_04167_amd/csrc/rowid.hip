@@ -137,6 +137,159 @@ __global__ __launch_bounds__(256) void id_step_kernel(IdLevelArgs a, int j, cons
     }
 }
 
+// The same decomposition from the Gram matrix G = A A^T of a node (msz x msz, built by a batched GEMM): pivoted
+// Cholesky of G picks the same rows as row-pivoted Gram-Schmidt of A and its factor holds the same coefficients
+// r_ij, but a step touches one row of G instead of every row of A.  One workgroup per node runs all steps:
+//   step j: p = argmax of the running diagonal d (rows not yet chosen), stop test as above with |a_p| = sqrt(d_p);
+//           l_i = (G[p][i] - sum_{q in panel} l_iq l_pq) / sqrt(d_p),  d_i -= l_i^2;
+//   after NB steps (a panel, kept in LDS) the coefficients go to Lc and G -= Lp Lp^T.
+// The diagonal is down-dated, so |a_p| carries an absolute error of about 1e-7 |a_p0|: the host uses this
+// kernel only when the relative stop threshold is well above that.
+template <int NB>
+__global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __restrict__ G, const int64_t* __restrict__ goff,
+                                                      int maxm) {
+    extern __shared__ double sm[];
+    constexpr int LDP = NB + 1;
+    const int node = blockIdx.x;
+    const int64_t m0 = a.moff[node];
+    const int msz = (int)(a.moff[node + 1] - m0);
+    const int lim = msz < a.kcap ? msz : a.kcap;
+    double* Gn = G + goff[node];
+    double* Lp = sm;                                    // [maxm][LDP]
+    double* red_v = sm + (size_t)maxm * LDP;            // [2][8]
+    int* red_i = reinterpret_cast<int*>(red_v + 16);    // [2][8]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i0 = tid, i1 = tid + 512;                 // the rows this thread owns
+    double d0 = i0 < msz ? Gn[(size_t)i0 * msz + i0] : 0.0;
+    double d1 = i1 < msz ? Gn[(size_t)i1 * msz + i1] : 0.0;
+    int s0 = 0, s1 = 0;                                 // step + 1 at which the row was chosen
+    double thr = 0.0;
+    int rank = 0, par = 0;
+    bool stop = false;
+    for (int p0 = 0; p0 < lim && !stop; p0 += NB) {
+        int nb = 0;
+        for (int jj = 0; jj < NB && p0 + jj < lim; ++jj) {
+            const int j = p0 + jj;
+            double bv = -1.0;
+            int bi = 0x7fffffff;
+            if (i0 < msz && s0 == 0 && d0 > bv) { bv = d0; bi = i0; }
+            if (i1 < msz && s1 == 0 && d1 > bv) { bv = d1; bi = i1; }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const double ov = __shfl_xor(bv, off, 64);
+                const int oi = __shfl_xor(bi, off, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (lane == 0) { red_v[par * 8 + wave] = bv; red_i[par * 8 + wave] = bi; }
+            __syncthreads();            // also orders the previous step's writes of Lp before this step's reads
+            bv = red_v[par * 8];
+            bi = red_i[par * 8];
+#pragma unroll
+            for (int w = 1; w < 8; ++w) {
+                const double ov = red_v[par * 8 + w];
+                const int oi = red_i[par * 8 + w];
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            par ^= 1;
+            if (bi >= msz) { stop = true; break; }      // no comparable value (NaN input)
+            const int p = bi;
+            const double pv = sqrt(bv > 0.0 ? bv : 0.0);
+            if (j == 0) {
+                thr = a.rel * pv;
+                if (a.abs_tol > thr) thr = a.abs_tol;
+                if (tid == 0) a.r11[node] = pv;
+            } else if (!(pv > thr)) {
+                stop = true;
+                break;
+            }
+            if (tid == 0) a.jtmp[(size_t)node * a.kc + j] = p;
+            const double inv = pv > 0.0 ? 1.0 / pv : 0.0;
+            const double* Lpp = Lp + (size_t)p * LDP;
+            const double* Gp = Gn + (size_t)p * msz;
+            if (i0 < msz) {
+                double l = 0.0;
+                if (i0 == p) { l = pv; s0 = j + 1; }
+                else if (s0 == 0) {
+                    double c = Gp[i0];
+                    const double* Li = Lp + (size_t)i0 * LDP;
+                    for (int q = 0; q < jj; ++q) c -= Li[q] * Lpp[q];
+                    l = c * inv;
+                    d0 -= l * l;
+                }
+                Lp[(size_t)i0 * LDP + jj] = l;
+            }
+            if (i1 < msz) {
+                double l = 0.0;
+                if (i1 == p) { l = pv; s1 = j + 1; }
+                else if (s1 == 0) {
+                    double c = Gp[i1];
+                    const double* Li = Lp + (size_t)i1 * LDP;
+                    for (int q = 0; q < jj; ++q) c -= Li[q] * Lpp[q];
+                    l = c * inv;
+                    d1 -= l * l;
+                }
+                Lp[(size_t)i1 * LDP + jj] = l;
+            }
+            rank = j + 1;
+            nb = jj + 1;
+        }
+        __syncthreads();
+        if (nb == 0) break;
+        // the panel's coefficients: rows of Lc, columns p0 .. p0 + nb
+        for (int i = tid; i < msz; i += 512) {
+            double* dst = a.Lc + (size_t)(m0 + i) * a.kc + p0;
+            const double* src = Lp + (size_t)i * LDP;
+            for (int q = 0; q < nb; ++q) dst[q] = src[q];
+        }
+        if (stop || p0 + nb >= lim) break;
+        // G -= Lp Lp^T: thread (ty, tx) of a 32 x 16 arrangement owns rows ty + 32 u and columns tx + 16 v of a
+        // 128 x 64 tile
+        const int ty = tid >> 4, tx = tid & 15;
+        for (int rb = 0; rb < msz; rb += 128)
+            for (int cb = 0; cb < msz; cb += 64) {
+                double acc[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[u][v] = 0.0;
+                const int rbase = rb + ty, cbase = cb + tx;
+                for (int q = 0; q < nb; ++q) {
+                    double av[4], bw[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int r = rbase + 32 * u;
+                        av[u] = Lp[(size_t)(r < msz ? r : 0) * LDP + q];
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int cc = cbase + 16 * v;
+                        bw[v] = Lp[(size_t)(cc < msz ? cc : 0) * LDP + q];
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) acc[u][v] += av[u] * bw[v];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int r = rbase + 32 * u;
+                    if (r >= msz) continue;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int cc = cbase + 16 * v;
+                        if (cc < msz) Gn[(size_t)r * msz + cc] -= acc[u][v];
+                    }
+                }
+            }
+        __threadfence_block();
+        __syncthreads();
+    }
+    // which step chose which row; rank
+    if (i0 < msz) a.sel[m0 + i0] = s0;
+    if (i1 < msz) a.sel[m0 + i1] = s1;
+    if (tid == 0) a.rk[node] = rank;
+}
+
 // T = L21 L11^{-1} row by row (one wavefront per row, the row's coefficients spread over the lanes),
 // and assembly of U (msz x k, row-major at uoff[node]) and of the compact skeleton list J.
 template <int KU>   // kc <= 64 * KU
@@ -245,6 +398,26 @@ int id_finish(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, cons
         case 5: case 6: case 7: case 8:
             hipLaunchKernelGGL(id_finish_kernel<8>, grid, dim3(256), 0, st, a, koff, uoff, U, J); break;
         default: return HSS_EUNSUPPORTED;
+    }
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+
+// All pivot steps of every node of the level from the nodes' Gram matrices (G: msz x msz per node at goff,
+// destroyed).  Fills Lc, jtmp, sel, rk, r11 like id_init + id_steps.
+int id_chol(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* G, const int64_t* goff_dev) {
+    if (nnodes <= 0) return HSS_OK;
+    if (maxmsz > 1024) return HSS_EUNSUPPORTED;
+    const int nb = maxmsz <= 512 ? 32 : 16;
+    const size_t smem = sizeof(double) * ((size_t)maxmsz * (nb + 1) + 16) + sizeof(int) * 16;
+    if (nb == 32) {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(id_chol_kernel<32>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        hipLaunchKernelGGL(id_chol_kernel<32>, dim3((unsigned)nnodes), dim3(512), smem, st, a, G, goff_dev, maxmsz);
+    } else {
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(id_chol_kernel<16>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        hipLaunchKernelGGL(id_chol_kernel<16>, dim3((unsigned)nnodes), dim3(512), smem, st, a, G, goff_dev, maxmsz);
     }
     HIP_TRY(hipGetLastError());
     return HSS_OK;
