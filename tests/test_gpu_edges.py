@@ -1,0 +1,121 @@
+"""The limits of the library's shapes (GPU only): feature counts 1, 28/29 (a padding boundary) and 96 (the
+maximum), leaf sizes 16 and 1024 (minimum and maximum), sample width 512 with the rank cap at its maximum 512
+(node sizes up to 1024, the solve kernel's widest block), and odd ranks (scalar-load kernels).  Each case checks
+S = K Omega, the mat-vec, the ULV solve and a short ADMM run against the oracle on the exported matrix."""
+import copy
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import admm as oadmm          # noqa: E402
+from oracle import hss as ohss            # noqa: E402
+from oracle import ulv as oulv            # noqa: E402
+from oracle.kernel import gaussian_kernel  # noqa: E402
+from oracle.tree import cluster_tree      # noqa: E402
+from paper_2108_04167_amd import binding, synth   # noqa: E402
+
+
+def _dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _with_features(w, r):
+    """The workload with r feature columns: a prefix of its own, or its columns followed by fresh normal ones."""
+    w = copy.copy(w)
+    have = w.F.shape[1]
+    if r <= have:
+        w.F, w.F_test = np.ascontiguousarray(w.F[:, :r]), np.ascontiguousarray(w.F_test[:, :r])
+    else:
+        g = np.random.default_rng(1234)
+        w.F = np.ascontiguousarray(np.hstack([w.F, g.standard_normal((w.F.shape[0], r - have))]))
+        w.F_test = np.ascontiguousarray(np.hstack([w.F_test, g.standard_normal((w.F_test.shape[0], r - have))]))
+    return w
+
+
+# name -> (cfg, n, leaf, s, r or None, h or None, options)
+EDGES = {
+    "one_feature": (1, 1024, 64, 128, 1, 0.5, {}),
+    "r28": (3, 1024, 64, 128, 28, None, {}),
+    "r29": (3, 1024, 64, 128, 29, None, {}),
+    "r96_max": (5, 1024, 128, 256, 96, None, {}),
+    "leaf16_min": (1, 512, 16, 128, None, None, {}),
+    "leaf1024_max": (4, 4096, 1024, 512, None, None, {}),
+    "rank_cap_512_max": (3, 4096, 512, 512, None, None, {"oversample": 0}),       # nodes of 1024 rows
+    "odd_ranks": (1, 1024, 64, 128, None, 6.0, {"max_rank": 37}),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGES))
+def test_edge_shape(name):
+    from gpu_helpers import oracle_hss_from_export
+    cfg, n, leaf, s, r, h, opts = EDGES[name]
+    w = synth.make_workload(cfg, n=n, leaf=leaf, s=s)
+    if r is not None:
+        w = _with_features(w, r)
+    if h is not None:
+        w.h = h
+    ctx = binding.Context()
+    for k, v in opts.items():
+        ctx.hss_set_i64(k, v)
+    F, y, Om = _dev(w.F), _dev(w.y), w.omega()
+    # S = K Omega against the oracle
+    S = ctx.hss_kernel_sample(F, w.h, _dev(Om)).cpu().numpy()
+    ref = gaussian_kernel(w.F, w.F, w.h) @ Om
+    assert np.abs(S - ref).max() <= 1e-12 * np.abs(ref).max()
+    ctx.hss_compress(F, y, w.h, w.leaf, w.tol, _dev(Om))
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    assert np.array_equal(perm, cluster_tree(w.F, w.leaf))
+    st = ctx.hss_stats()
+    if name == "rank_cap_512_max":
+        assert st["rank_cap"] == 512 and exp["sizes"].max() == 1024
+    if name == "odd_ranks":
+        assert (exp["ranks"][1:] % 2 == 1).any()
+    H = oracle_hss_from_export(exp)
+    rng = np.random.default_rng(0)
+    v = rng.standard_normal(w.n)
+    mv = ctx.hss_matvec(_dev(v)).cpu().numpy()
+    mref = np.empty(w.n)
+    mref[perm] = ohss.matvec(H, v[perm])
+    assert _rel(mv, mref) <= 1e-12
+    ctx.hss_ulv_factor(w.beta)
+    x = _dev(v)
+    ctx.hss_ulv_solve(x)
+    Fz = oulv.ulv_factor(H, w.beta)
+    xref = np.empty(w.n)
+    xref[perm] = oulv.ulv_solve(Fz, v[perm])
+    assert _rel(x.cpu().numpy(), xref) <= 1e-10
+    out = ctx.admm_svm_train(w.C, w.beta, 15)
+    oref = oadmm.admm(lambda t: oulv.ulv_solve(Fz, t), w.y[perm], w.C, w.beta, 15)
+    for key in ("x", "z", "mu"):
+        assert _rel(out[key].cpu().numpy()[perm], oref[key]) <= 1e-6, key
+    G = w.F_test[:64]
+    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
+    dref = oadmm.decision(w.F[perm], w.y[perm], oref["z"], out["bias"], G, w.h)
+    assert np.abs(dec - dref).max() <= 1e-6 * max(1.0, np.abs(dref).max())
+    ctx.close()
+
+
+def test_limits_are_rejected_not_run():
+    w = synth.make_workload(1, n=2048, leaf=64, s=128)
+    ctx = binding.Context()
+    y = _dev(w.y)
+    wide = _dev(np.zeros((2048, 97)))
+    with pytest.raises(binding.HssError) as e:
+        ctx.hss_compress(wide, y, 1.0, 64, 1e-3)
+    assert e.value.code == binding.HSS_EUNSUPPORTED
+    with pytest.raises(binding.HssError) as e:            # leaf above 1024
+        ctx.hss_compress(_dev(w.F), y, 1.0, 2048, 1e-3)
+    assert e.value.code == binding.HSS_EUNSUPPORTED
+    ctx.hss_set_i64("sample_width", 640)
+    with pytest.raises(binding.HssError) as e:
+        ctx.hss_compress(_dev(w.F), y, 1.0, 64, 1e-3)
+    assert e.value.code == binding.HSS_EUNSUPPORTED
+    ctx.close()
