@@ -189,6 +189,8 @@ def main():
     # a plain copy of known size); they hold for the default workload and the kernels they were taken on only.
     traffic = MEASURED_TRAFFIC_BYTES.get((args.cfg, n), {})
 
+    rel_err = ctx.hss_error_estimate(8, 1)     # achieved ||K~ - K||_F / ||K||_F on 8 probe vectors (not timed)
+
     rec = {
         "metric": "admm_hss_train_seconds", "value": per_step, "unit": "s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
@@ -206,6 +208,7 @@ def main():
                            "bytes_per_solve": st2["factor_bytes"], "bytes_per_solve_compact": st2["factor_bytes_compact"],
                            "seconds_per_iteration": t_solve_iter, "seconds_per_solve_median_of_64": t_solve_median},
         "model": {"delta": st["delta"], "rank_max": st["rank_max"], "nodes_at_cap": st["nodes_at_cap"],
+                  "rel_error_estimate": rel_err,
                   "bias": out["bias"], "n_margin": out["n_margin"], "test_accuracy_pct": acc, "warnings": st2["warnings"]},
     }
     if not args.no_cpu_baseline:

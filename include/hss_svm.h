@@ -94,6 +94,13 @@ int hss_compress(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t
 int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r,
                               double h, int32_t leaf, double tol, const double* Omega_dev, int32_t s);
 
+/* Achieved compression error, estimated on nprobe (1..128) Gaussian probe vectors z_j drawn by the library's
+ * counter-based generator from `seed`:  sqrt( sum_j ||K~ z_j - K z_j||^2 / sum_j ||K z_j||^2 ), an estimate of
+ * ||K~ - K||_F / ||K||_F (the quantity the tolerance of Sec. 3.2 / eq. (9) speaks of), with K z_j from the exact
+ * kernel (one pass of the sampling kernel over a 128-column block) and K~ without the guard's shift.
+ * rel_err_out (host).  Needs a compressed context.  Synchronous. */
+int hss_error_estimate(hss_ctx* ctx, int32_t nprobe, uint64_t seed, double* rel_err_out);
+
 /* ULV factorization of K~ + beta I (Algorithm 3, lines 2-3).  beta > 0.  May be called again with another
  * beta without recompressing; replaces the previous factors. */
 int hss_ulv_factor(hss_ctx* ctx, double beta);

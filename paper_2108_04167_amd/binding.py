@@ -37,6 +37,7 @@ ABI = {
     "hss_compress": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32, C.c_double]),
     "hss_compress_with_samples": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32,
                                             C.c_double, c_dp, C.c_int32]),
+    "hss_error_estimate": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.POINTER(C.c_double)]),
     "hss_ulv_factor": (C.c_int, [C.c_void_p, C.c_double]),
     "hss_ulv_solve": (C.c_int, [C.c_void_p, c_dp, C.c_int32]),
     "hss_matvec": (C.c_int, [C.c_void_p, c_dp, c_dp]),
@@ -247,3 +248,8 @@ class Context:
         rc = _check(_lib.admm_svm_train_multi(self._h, cl, nC, float(beta), int(maxit), _ptr(x), _ptr(z), _ptr(mu),
                                               bias, cnt), "admm_svm_train_multi")
         return {"x": x, "z": z, "mu": mu, "bias": list(bias), "n_margin": list(cnt), "warnings": rc}
+
+    def hss_error_estimate(self, nprobe=16, seed=1):
+        out = C.c_double(0.0)
+        _check(_lib.hss_error_estimate(self._h, int(nprobe), int(seed), C.byref(out)), "hss_error_estimate")
+        return out.value

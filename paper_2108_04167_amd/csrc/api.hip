@@ -1,6 +1,7 @@
 // C ABI of libhsssvm (see include/hss_svm.h for the contract of every call).
 #include "ctx.h"
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 
 extern "C" {
@@ -89,6 +90,42 @@ int hss_import(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n
                const int64_t* perm, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
                const int32_t* J, const double* B, double delta) {
     return hss_import_impl(ctx, F_dev, y_dev, n, r, h, leaf, perm, sizes, ranks, D, U, J, B, delta);
+}
+
+int hss_error_estimate(hss_ctx* c, int32_t nprobe, uint64_t seed, double* rel_err_out) {
+    if (!c || !rel_err_out || nprobe < 1 || nprobe > 128) return HSS_EINVAL;
+    if (!c->compressed) return HSS_ESTATE;
+    hipStream_t st = c->stream;
+    const int64_t n = c->n, n_pad = c->n_pad;
+    const int sp = 128;                               // narrowest block the sampling kernel takes
+    DevBuf Z, KZ, t, r;
+    HSS_TRY(Z.reserve(sizeof(double) * n_pad * sp));
+    HSS_TRY(KZ.reserve(sizeof(double) * n_pad * sp));
+    HSS_TRY(t.reserve(sizeof(double) * n));
+    HSS_TRY(r.reserve(sizeof(double) * n));
+    HSS_TRY(omega_fill_launch(st, Z.as<double>(), n, n_pad, nprobe, sp, seed));
+    HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Z.as<double>(), KZ.as<double>(), n_pad, c->r_pad, sp,
+                          c->h));
+    double* part = c->partial.as<double>();
+    double* scal = c->scal.as<double>();
+    double num = 0.0, den = 0.0;
+    for (int j = 0; j < nprobe; ++j) {
+        HSS_TRY(vec_column(st, c->mv_x.as<double>(), Z.as<double>(), n, sp, j));
+        HSS_TRY(hss_matvec_perm(c));                                    // mv_y = (K~ + delta I) z
+        HSS_TRY(vec_column(st, t.as<double>(), KZ.as<double>(), n, sp, j));      // t = K z
+        HIP_TRY(hipMemcpyAsync(r.p, c->mv_y.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
+        if (c->delta != 0.0) HSS_TRY(vec_axpby(st, r.as<double>(), c->mv_x.as<double>(), -c->delta, 1.0, n));
+        HSS_TRY(vec_axpby(st, r.as<double>(), t.as<double>(), -1.0, 1.0, n));    // r = K~ z - K z
+        HSS_TRY(vec_dot(st, r.as<double>(), r.as<double>(), n, part, scal));
+        HSS_TRY(vec_dot(st, t.as<double>(), t.as<double>(), n, part, scal + 1));
+        double two[2];
+        HIP_TRY(hipMemcpyAsync(two, scal, sizeof(two), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        num += two[0];
+        den += two[1];
+    }
+    *rel_err_out = den > 0.0 ? std::sqrt(num / den) : 0.0;
+    return HSS_OK;
 }
 
 int hss_ulv_factor(hss_ctx* ctx, double beta) { return ulv_factor_impl(ctx, beta); }

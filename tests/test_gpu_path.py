@@ -121,6 +121,32 @@ def test_guard_makes_the_matrix_definite(case):
         assert lam0 < 0 and st["delta"] <= 1.25 * (-lam0)
 
 
+def test_error_estimate_matches_dense_definition(case):
+    """The library's estimate against its definition written out with the dense kernel and the densified
+    exported matrix, on the probe vectors the library draws (generator hook)."""
+    import ctypes as C
+    import torch
+    from gpu_helpers import lib, oracle_hss_from_export, ptr
+    w = case.w
+    if w.n > 2048:
+        pytest.skip("dense comparison only for small n")
+    nprobe, seed = 5, 77
+    est = case.ctx.hss_error_estimate(nprobe, seed)
+    L = lib()
+    Z = torch.empty((w.n, nprobe), dtype=torch.float64, device="cuda:0")
+    L.hsx_omega.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_uint64]
+    assert L.hsx_omega(None, ptr(Z), w.n, nprobe, seed) == 0
+    Z = Z.cpu().numpy()                                  # rows in cluster-tree order
+    Fp = w.F[case.perm]
+    K = gaussian_kernel(Fp, Fp, w.h)
+    Kt = ohss.densify(oracle_hss_from_export(case.exp, with_shift=False))
+    ref = np.linalg.norm((Kt - K) @ Z) / np.linalg.norm(K @ Z)
+    assert abs(est - ref) <= 1e-9 * max(ref, 1e-6) + 1e-13
+    # and it estimates the relative Frobenius error
+    fro = np.linalg.norm(Kt - K) / np.linalg.norm(K)
+    assert 0.2 * fro <= case.ctx.hss_error_estimate(64, 3) <= 5.0 * fro + 1e-12
+
+
 def test_matvec_matches_oracle_on_the_exported_matrix(case):
     rng = np.random.default_rng(1)
     x = rng.standard_normal(case.w.n)
