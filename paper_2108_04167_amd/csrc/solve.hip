@@ -40,9 +40,11 @@ __device__ __forceinline__ double* scaled(double* p, double* pool) {
     return (NR == 1 || p == nullptr) ? p : pool + (p - pool) * NR;
 }
 
-template <int R, bool VEC, int NR>
+// A workgroup walks over `reps` groups of 4R rows (the work list is cut for 4 R reps rows), so that its start-up
+// (two dependent descriptor loads) is paid once per reps row groups.
+template <int R, bool VEC, int NR, int NCH>
 __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __restrict__ items,
-                                                         const int2* __restrict__ work, double* pool) {
+                                                         const int2* __restrict__ work, double* pool, int reps) {
     const int2 w = work[blockIdx.x];
     const SolveItem it = items[w.x];
     const int m = it.m;
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
     double* out0 = scaled<NR>(it.out0, pool);
     double* out1 = scaled<NR>(it.out1, pool);
     if (it.M == nullptr) {   // nothing was eliminated at this node: hand the vectors through
-        const int lo = w.y * NR, hi = (w.y + 4 * R < m ? w.y + 4 * R : m) * NR;
+        const int lo = w.y * NR, hi = (w.y + 4 * R * reps < m ? w.y + 4 * R * reps : m) * NR;
         for (int e = lo + tid; e < hi; e += 256) {
             const double v = e < it.n0 * NR ? in0[e] : in1[e - it.n0 * NR];
             if (e < it.nout0 * NR) out0[e] = v;
@@ -60,7 +62,8 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
         }
         return;
     }
-    const int row0 = w.y + wave * R;
+  for (int rep = 0; rep < reps; ++rep) {
+    const int row0 = w.y + (rep * 4 + wave) * R;
     if (row0 >= m) return;
     constexpr int KMAX = 16;   // m <= 1024
     double s[R][NR];
@@ -71,7 +74,40 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
     const double* rowp[R];
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) rowp[rr] = it.M + (size_t)(row0 + rr < m ? row0 + rr : m - 1) * it.ld;
-    if (VEC) {
+    if constexpr (VEC && NCH > 0) {
+        // the lane's share of X first (all column chunks), then the matrix rows one after the other: a wavefront
+        // reads each row front to back, which the memory system serves measurably faster than chunk-major order
+        double x0[NCH][NR], x1[NCH][NR];
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            const int c = 2 * lane + 128 * k;
+#pragma unroll
+            for (int j = 0; j < NR; ++j) x0[k][j] = x1[k][j] = 0.0;
+            if (c < m) {            // c and n0 are even: both columns come from the same input
+                const double* src = c < it.n0 ? in0 + (size_t)c * NR : in1 + (size_t)(c - it.n0) * NR;
+#pragma unroll
+                for (int q = 0; q < NR; ++q) {      // 2 NR consecutive doubles, 16 bytes at a time
+                    const double2 t = *reinterpret_cast<const double2*>(src + 2 * q);
+                    if (2 * q < NR) x0[k][2 * q] = t.x; else x1[k][2 * q - NR] = t.x;
+                    if (2 * q + 1 < NR) x0[k][2 * q + 1] = t.y; else x1[k][2 * q + 1 - NR] = t.y;
+                }
+            }
+        }
+#pragma unroll
+        for (int rr = 0; rr < R; ++rr) {
+#pragma unroll
+            for (int k = 0; k < NCH; ++k) {
+                // no branch around the loads (a chunk past the end of a short row re-reads its start against
+                // zeros): the compiler keeps all of them in flight
+                const int c = 2 * lane + 128 * k;
+                const int cc = c < m ? c : 0;
+                // streamed once per sweep: non-temporal, so the factors do not displace the vectors in cache
+                const v2d a = __builtin_nontemporal_load(reinterpret_cast<const v2d*>(rowp[rr] + cc));
+#pragma unroll
+                for (int j = 0; j < NR; ++j) s[rr][j] += a.x * x0[k][j] + a.y * x1[k][j];
+            }
+        }
+    } else if (VEC) {
 #pragma unroll
         for (int k = 0; k < KMAX / 2; ++k) {
             const int c = 2 * lane + 128 * k;
@@ -136,13 +172,14 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
             }
         }
     }
+  }
 }
 
 // Batched y = alpha * A x + beta * y for the HSS mat-vec, A (M x N, N <= 1024) row-major: a wavefront computes
 // four consecutive rows with the input vector in registers, as in the solve kernel; transposed products use a
 // transposed copy of the generator, so every product streams rows.  Items whose generator is a permutation
 // (a node that kept all its rows) only move entries.
-template <bool VEC>
+template <bool VEC, int NCH>    // NCH: 128-column chunks covering the widest item (16-byte loads only)
 __global__ __launch_bounds__(256) void bgemv_rows_kernel(const GemvItem* __restrict__ items, double alpha, double beta) {
     const GemvItem it = items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -162,18 +199,21 @@ __global__ __launch_bounds__(256) void bgemv_rows_kernel(const GemvItem* __restr
 #pragma unroll
         for (int rr = 0; rr < R; ++rr) rowp[rr] = it.A + (size_t)(row0 + rr < it.M ? row0 + rr : it.M - 1) * it.lda;
         if (VEC) {
+            // row by row, no branch around the loads (see the solve kernel)
+            double2 xv[NCH];
 #pragma unroll
-            for (int k = 0; k < KMAX / 2; ++k) {
+            for (int k = 0; k < NCH; ++k) {
                 const int c = 2 * lane + 128 * k;
-                if (128 * k < N) {          // uniform
-                    double2 xv = make_double2(0.0, 0.0);
-                    if (c < N) xv = *reinterpret_cast<const double2*>(it.x + c);
-                    const int cc = c < N ? c : 0;
+                xv[k] = make_double2(0.0, 0.0);
+                if (c < N) xv[k] = *reinterpret_cast<const double2*>(it.x + c);
+            }
 #pragma unroll
-                    for (int rr = 0; rr < R; ++rr) {
-                        const v2d a = *reinterpret_cast<const v2d*>(rowp[rr] + cc);
-                        s[rr] += a.x * xv.x + a.y * xv.y;
-                    }
+            for (int rr = 0; rr < R; ++rr) {
+#pragma unroll
+                for (int k = 0; k < NCH; ++k) {
+                    const int c = 2 * lane + 128 * k;
+                    const v2d a = *reinterpret_cast<const v2d*>(rowp[rr] + (c < N ? c : 0));
+                    s[rr] += a.x * xv[k].x + a.y * xv[k].y;
                 }
             }
         } else {
@@ -201,13 +241,19 @@ __global__ __launch_bounds__(256) void bgemv_rows_kernel(const GemvItem* __restr
 }  // namespace
 
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
-                       bool vec, int nrhs, double* pool) {
+                       int reps, bool vec, int nrhs, double* pool, int maxm) {
+    if (maxm > 1024) return HSS_EUNSUPPORTED;
     if (nwork <= 0) return HSS_OK;
     dim3 g((unsigned)nwork), b(256);
-#define HSS_SOLVE_GO(R, NR)                                                                                       \
-    do {                                                                                                          \
-        if (vec) hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR>), g, b, 0, st, items_dev, work_dev, pool);    \
-        else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR>), g, b, 0, st, items_dev, work_dev, pool);       \
+#define HSS_SOLVE_K(R, NR, NCH)                                                                                  \
+    hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR, NCH>), g, b, 0, st, items_dev, work_dev, pool, reps)
+#define HSS_SOLVE_GO(R, NR)                                                                                      \
+    do {                                                                                                         \
+        if (vec && NR == 1 && nch == 2) HSS_SOLVE_K(R, 1, 2);                                                    \
+        else if (vec && NR == 1 && nch == 4) HSS_SOLVE_K(R, 1, 4);                                               \
+        else if (vec && NR == 1 && nch == 8) HSS_SOLVE_K(R, 1, 8);                                               \
+        else if (vec) HSS_SOLVE_K(R, NR, 0);                                                                     \
+        else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR, 0>), g, b, 0, st, items_dev, work_dev, pool, reps); \
     } while (0)
 #define HSS_SOLVE_CASE(R)                                                                                         \
     case R:                                                                                                       \
@@ -216,6 +262,8 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
         else HSS_SOLVE_GO(R, 4);                                                                                  \
         break;
     if (nrhs != 1 && nrhs != 2 && nrhs != 4) return HSS_EINVAL;
+    // one right-hand side, 16-byte loads: the row-by-row variant unrolled for the level's widest node
+    const int nch = maxm <= 256 ? 2 : (maxm <= 512 ? 4 : 8);
     switch (rows_per_wave) {
         HSS_SOLVE_CASE(1)
         HSS_SOLVE_CASE(2)
@@ -224,6 +272,7 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
         default: return HSS_EINVAL;
     }
 #undef HSS_SOLVE_CASE
+#undef HSS_SOLVE_K
 #undef HSS_SOLVE_GO
     HIP_TRY(hipGetLastError());
     return HSS_OK;
@@ -236,10 +285,11 @@ int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM
     // enough workgroups to fill the chip, at most one per 16 rows
     int yc = (maxM + 15) / 16;
     while (yc > 1 && (int64_t)nitems * yc > 16384) yc = (yc + 1) / 2;
-    if (vec) hipLaunchKernelGGL(bgemv_rows_kernel<true>, dim3((unsigned)nitems, (unsigned)yc), dim3(256), 0, st, items_dev,
-                                alpha, beta);
-    else hipLaunchKernelGGL(bgemv_rows_kernel<false>, dim3((unsigned)nitems, (unsigned)yc), dim3(256), 0, st, items_dev,
-                            alpha, beta);
+    const dim3 g((unsigned)nitems, (unsigned)yc), b(256);
+    if (!vec) hipLaunchKernelGGL((bgemv_rows_kernel<false, 1>), g, b, 0, st, items_dev, alpha, beta);
+    else if (maxN <= 256) hipLaunchKernelGGL((bgemv_rows_kernel<true, 2>), g, b, 0, st, items_dev, alpha, beta);
+    else if (maxN <= 512) hipLaunchKernelGGL((bgemv_rows_kernel<true, 4>), g, b, 0, st, items_dev, alpha, beta);
+    else hipLaunchKernelGGL((bgemv_rows_kernel<true, 8>), g, b, 0, st, items_dev, alpha, beta);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }

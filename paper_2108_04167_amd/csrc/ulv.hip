@@ -101,11 +101,15 @@ int build_solve_tables(hss_ctx* c) {
             rows_total += lv.msz[t];
             if ((lv.msz[t] | lv.rk[t]) & 1) even = false;
         }
-        int rpw = 8;
+        // measured on the widest level of the n = 262144 workload (1.07 GB per sweep): 2 rows per wavefront
+        // 157 us, 4 rows 163 us, 8 rows 177 us -- many short-lived workgroups beat few long ones here
+        int rpw = 2;
         while (rpw > 1 && rows_total / (4 * rpw) < 4096) rpw >>= 1;
         lv.rows_per_wave = rpw;
+        const int reps = 1;
+        lv.reps = reps;
         lv.vec = even;
-        const int rb = 4 * rpw;
+        const int rb = 4 * rpw * reps;
         for (int t = 0; t < lv.N; ++t) {
             const int m = lv.msz[t], k = lv.rk[t];
             if (l == 0) {
@@ -437,19 +441,19 @@ int ulv_solve_inplace(hss_ctx* c, int nrhs) {
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
-        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec,
-                                   nrhs, pool));
+        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.reps, lv.vec,
+                                   nrhs, pool, lv.maxm));
     }
     {
         Level& rl = c->lev[0];
-        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.vec,
-                                   nrhs, pool));
+        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.reps, rl.vec,
+                                   nrhs, pool, rl.maxm));
     }
     for (int l = 1; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
         HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave,
-                                   lv.vec, nrhs, pool));
+                                   lv.reps, lv.vec, nrhs, pool, lv.maxm));
     }
     return HSS_OK;
 }
