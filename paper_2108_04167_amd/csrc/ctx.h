@@ -33,8 +33,8 @@ struct Level {
                                             // layout): input (sum msz), eliminated part (sum msz-rk), output (sum msz)
     DevBuf up_items, down_items, work;      // SolveItem tables and the (node, row block) work list
     int nwork = 0;
-    int rows_per_wave = 4, reps = 1;        // launch shape of the level's solve kernel: a workgroup takes
-                                            // 4 * rows_per_wave * reps rows of one node
+    int rows_per_wave = 2;                  // launch shape of the level's solve kernel: a workgroup takes
+                                            // 4 * rows_per_wave rows of one node
     bool vec = false;                       // 16-byte loads allowed (all sizes even)
     bool skip = false;                      // leaf level where no node eliminates anything: the level above reads
                                             // and writes the leaf vectors directly and no kernel is launched

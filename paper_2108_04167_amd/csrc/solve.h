@@ -21,12 +21,12 @@ struct GemvItem {            // y = alpha * op x + beta * y
     int32_t M, N, lda, mode;
 };
 
-// rows_per_wave in {1, 2, 4, 8}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
+// rows_per_wave in {1, 2}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
 // nrhs in {1, 2, 4} interleaved right-hand sides; `pool` is the allocation all vector pointers of the item
 // tables point into (a pointer p of the tables stands for pool + (p - pool) * nrhs).
-// A work item stands for 4 * rows_per_wave * reps rows; maxm = widest node of the table (<= 1024).
+// A work item stands for 4 * rows_per_wave rows; maxm = widest node of the table (<= 1024).
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
-                       int reps, bool vec, int nrhs, double* pool, int maxm);
+                       bool vec, int nrhs, double* pool, int maxm);
 // vec: every M, N, lda of the table is even and every pointer 16-byte aligned
 int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool vec, double alpha,
                  double beta);

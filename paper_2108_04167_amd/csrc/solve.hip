@@ -22,10 +22,12 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-// One wavefront computes R consecutive rows of Y = M X for one node and NR right-hand sides; the input
-// vectors live in registers (lane l holds the columns it multiplies), so a wavefront issues its loads of X
-// and of its R matrix rows back to back and waits once, and every matrix entry is used NR times.
+// One wavefront computes R consecutive rows of Y = M X for one node and NR right-hand sides; lane l multiplies
+// columns 2l, 2l+1 (+128 per chunk) of every row, and every matrix entry is used NR times.
 // VEC: 16-byte loads (needs even m, n0, ld and 16-byte aligned pointers).
+// NCH > 0 (VEC only): the level's widest node has at most 128 NCH columns; the lane's share of X is loaded
+// first, then the rows are streamed front to back without a branch between the loads.  NCH = 0: chunk by
+// chunk over all rows, any width up to 1024.
 // A workgroup = 4 wavefronts = 4R rows; the work list gives (node, first row).
 //
 // Right-hand sides are interleaved: entry i of column j sits at v[i * NR + j].  The item tables hold the
@@ -40,11 +42,9 @@ __device__ __forceinline__ double* scaled(double* p, double* pool) {
     return (NR == 1 || p == nullptr) ? p : pool + (p - pool) * NR;
 }
 
-// A workgroup walks over `reps` groups of 4R rows (the work list is cut for 4 R reps rows), so that its start-up
-// (two dependent descriptor loads) is paid once per reps row groups.
 template <int R, bool VEC, int NR, int NCH>
 __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __restrict__ items,
-                                                         const int2* __restrict__ work, double* pool, int reps) {
+                                                         const int2* __restrict__ work, double* pool) {
     const int2 w = work[blockIdx.x];
     const SolveItem it = items[w.x];
     const int m = it.m;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
     double* out0 = scaled<NR>(it.out0, pool);
     double* out1 = scaled<NR>(it.out1, pool);
     if (it.M == nullptr) {   // nothing was eliminated at this node: hand the vectors through
-        const int lo = w.y * NR, hi = (w.y + 4 * R * reps < m ? w.y + 4 * R * reps : m) * NR;
+        const int lo = w.y * NR, hi = (w.y + 4 * R < m ? w.y + 4 * R : m) * NR;
         for (int e = lo + tid; e < hi; e += 256) {
             const double v = e < it.n0 * NR ? in0[e] : in1[e - it.n0 * NR];
             if (e < it.nout0 * NR) out0[e] = v;
@@ -62,8 +62,7 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
         }
         return;
     }
-  for (int rep = 0; rep < reps; ++rep) {
-    const int row0 = w.y + (rep * 4 + wave) * R;
+    const int row0 = w.y + wave * R;
     if (row0 >= m) return;
     constexpr int KMAX = 16;   // m <= 1024
     double s[R][NR];
@@ -172,7 +171,6 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
             }
         }
     }
-  }
 }
 
 // Batched y = alpha * A x + beta * y for the HSS mat-vec, A (M x N, N <= 1024) row-major: a wavefront computes
@@ -241,19 +239,19 @@ __global__ __launch_bounds__(256) void bgemv_rows_kernel(const GemvItem* __restr
 }  // namespace
 
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
-                       int reps, bool vec, int nrhs, double* pool, int maxm) {
+                       bool vec, int nrhs, double* pool, int maxm) {
     if (maxm > 1024) return HSS_EUNSUPPORTED;
     if (nwork <= 0) return HSS_OK;
     dim3 g((unsigned)nwork), b(256);
 #define HSS_SOLVE_K(R, NR, NCH)                                                                                  \
-    hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR, NCH>), g, b, 0, st, items_dev, work_dev, pool, reps)
+    hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR, NCH>), g, b, 0, st, items_dev, work_dev, pool)
 #define HSS_SOLVE_GO(R, NR)                                                                                      \
     do {                                                                                                         \
         if (vec && NR == 1 && nch == 2) HSS_SOLVE_K(R, 1, 2);                                                    \
         else if (vec && NR == 1 && nch == 4) HSS_SOLVE_K(R, 1, 4);                                               \
         else if (vec && NR == 1 && nch == 8) HSS_SOLVE_K(R, 1, 8);                                               \
         else if (vec) HSS_SOLVE_K(R, NR, 0);                                                                     \
-        else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR, 0>), g, b, 0, st, items_dev, work_dev, pool, reps); \
+        else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR, 0>), g, b, 0, st, items_dev, work_dev, pool); \
     } while (0)
 #define HSS_SOLVE_CASE(R)                                                                                         \
     case R:                                                                                                       \
@@ -267,8 +265,6 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
     switch (rows_per_wave) {
         HSS_SOLVE_CASE(1)
         HSS_SOLVE_CASE(2)
-        HSS_SOLVE_CASE(4)
-        HSS_SOLVE_CASE(8)
         default: return HSS_EINVAL;
     }
 #undef HSS_SOLVE_CASE

@@ -106,10 +106,8 @@ int build_solve_tables(hss_ctx* c) {
         int rpw = 2;
         while (rpw > 1 && rows_total / (4 * rpw) < 4096) rpw >>= 1;
         lv.rows_per_wave = rpw;
-        const int reps = 1;
-        lv.reps = reps;
         lv.vec = even;
-        const int rb = 4 * rpw * reps;
+        const int rb = 4 * rpw;
         for (int t = 0; t < lv.N; ++t) {
             const int m = lv.msz[t], k = lv.rk[t];
             if (l == 0) {
@@ -441,19 +439,19 @@ int ulv_solve_inplace(hss_ctx* c, int nrhs) {
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
-        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.reps, lv.vec,
+        HSS_TRY(solve_level_launch(st, lv.up_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave, lv.vec,
                                    nrhs, pool, lv.maxm));
     }
     {
         Level& rl = c->lev[0];
-        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.reps, rl.vec,
+        HSS_TRY(solve_level_launch(st, rl.up_items.as<SolveItem>(), rl.work.as<int2>(), rl.nwork, rl.rows_per_wave, rl.vec,
                                    nrhs, pool, rl.maxm));
     }
     for (int l = 1; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
         HSS_TRY(solve_level_launch(st, lv.down_items.as<SolveItem>(), lv.work.as<int2>(), lv.nwork, lv.rows_per_wave,
-                                   lv.reps, lv.vec, nrhs, pool, lv.maxm));
+                                   lv.vec, nrhs, pool, lv.maxm));
     }
     return HSS_OK;
 }
