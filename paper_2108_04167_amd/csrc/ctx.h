@@ -33,6 +33,8 @@ struct Level {
                                             // layout): input (sum msz), eliminated part (sum msz-rk), output (sum msz)
     DevBuf up_items, down_items, work;      // SolveItem tables and the (node, row block) work list
     int nwork = 0;
+    DevBuf work_wide;                       // the same for four interleaved right-hand sides (16-row blocks)
+    int nwork_wide = 0;
     int rows_per_wave = 2;                  // launch shape of the level's solve kernel: a workgroup takes
                                             // 4 * rows_per_wave rows of one node
     bool vec = false;                       // 16-byte loads allowed (all sizes even)

@@ -21,7 +21,7 @@ struct GemvItem {            // y = alpha * op x + beta * y
     int32_t M, N, lda, mode;
 };
 
-// rows_per_wave in {1, 2}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
+// rows_per_wave in {1, 2, 4}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
 // nrhs in {1, 2, 4} interleaved right-hand sides; `pool` is the allocation all vector pointers of the item
 // tables point into (a pointer p of the tables stands for pool + (p - pool) * nrhs).
 // A work item stands for 4 * rows_per_wave rows; maxm = widest node of the table (<= 1024).

@@ -247,8 +247,8 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
     hipLaunchKernelGGL((solve_gemv_kernel<R, true, NR, NCH>), g, b, 0, st, items_dev, work_dev, pool)
 #define HSS_SOLVE_GO(R, NR)                                                                                      \
     do {                                                                                                         \
-        if (vec && NR == 1 && nch == 2) HSS_SOLVE_K(R, 1, 2);                                                    \
-        else if (vec && NR == 1 && nch == 4) HSS_SOLVE_K(R, 1, 4);                                               \
+        if (vec && (NR == 1 || R == 4) && nch == 2) HSS_SOLVE_K(R, NR, 2);                                       \
+        else if (vec && (NR == 1 || R == 4) && nch == 4) HSS_SOLVE_K(R, NR, 4);                                  \
         else if (vec && NR == 1 && nch == 8) HSS_SOLVE_K(R, 1, 8);                                               \
         else if (vec) HSS_SOLVE_K(R, NR, 0);                                                                     \
         else hipLaunchKernelGGL((solve_gemv_kernel<R, false, NR, 0>), g, b, 0, st, items_dev, work_dev, pool); \
@@ -265,6 +265,7 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
     switch (rows_per_wave) {
         HSS_SOLVE_CASE(1)
         HSS_SOLVE_CASE(2)
+        HSS_SOLVE_CASE(4)
         default: return HSS_EINVAL;
     }
 #undef HSS_SOLVE_CASE
