@@ -1,0 +1,96 @@
+"""Seeded random small problems through the whole path (GPU only): tree, compression, mat-vec, ULV solve and ADMM
+against the oracle on the exported matrix, over leaf sizes that are not powers of two, feature counts across the
+padding classes, both forms of the interpolative decomposition (tolerances on both sides of their switch), rank caps
+that cut or do not cut, guard on and off."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import admm as oadmm          # noqa: E402
+from oracle import hss as ohss            # noqa: E402
+from oracle import ulv as oulv            # noqa: E402
+from oracle.kernel import gaussian_kernel  # noqa: E402
+from oracle.tree import cluster_tree      # noqa: E402
+from paper_2108_04167_amd import binding   # noqa: E402
+
+
+def _dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _draw(seed):
+    g = np.random.default_rng(1000 + seed)
+    leaf = int(g.choice([16, 32, 48, 64, 80, 96, 128, 176]))
+    L = int(g.integers(0, 5))
+    n = leaf << L
+    r = int(g.choice([1, 2, 3, 5, 8, 13, 27, 28, 29, 40, 56, 57, 70, 84, 85, 96]))
+    s = int(g.choice([32, 100, 128, 200, 256]))
+    F = g.standard_normal((n, r)) * g.uniform(0.3, 2.0, size=r)
+    if g.random() < 0.3:                      # some binary columns: exact ties in the tree
+        k = max(1, r // 3)
+        F[:, :k] = (g.random((n, k)) < 0.3).astype(np.float64)
+    y = np.where(g.random(n) < 0.5, -1.0, 1.0)
+    h = float(np.sqrt(r) * g.choice([0.5, 1.0, 3.0, 10.0]))
+    tol = float(g.choice([1e-2, 1e-3, 1e-4, 3e-5, 1e-5, 1e-6]))
+    opts = {}
+    if g.random() < 0.4:
+        opts["max_rank"] = int(g.integers(3, max(4, min(s, 2 * leaf))))
+    if g.random() < 0.2:
+        opts["psd_guard"] = 0
+    C = float(g.choice([0.1, 1.0, 10.0]))
+    beta = float(g.choice([0.5, 1.0, 4.0]))
+    Om = g.standard_normal((n, s))
+    return dict(n=n, leaf=leaf, r=r, s=s, F=F, y=y, h=h, tol=tol, opts=opts, C=C, beta=beta, Om=Om)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_problem(seed):
+    from gpu_helpers import oracle_hss_from_export
+    p = _draw(seed)
+    n = p["n"]
+    ctx = binding.Context()
+    for k, v in p["opts"].items():
+        ctx.hss_set_i64(k, v)
+    F, y = _dev(p["F"]), _dev(p["y"])
+    S = ctx.hss_kernel_sample(F, p["h"], _dev(p["Om"])).cpu().numpy()
+    ref = gaussian_kernel(p["F"], p["F"], p["h"]) @ p["Om"]
+    assert np.abs(S - ref).max() <= 1e-12 * max(np.abs(ref).max(), 1e-300)
+    ctx.hss_compress(F, y, p["h"], p["leaf"], p["tol"], _dev(p["Om"]))
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    assert np.array_equal(perm, cluster_tree(p["F"], p["leaf"])), "tree"
+    H = oracle_hss_from_export(exp)
+    # the exported bases are interpolative on their skeleton rows and the ranks respect the cap
+    st = ctx.hss_stats()
+    assert exp["ranks"].max() <= st["rank_cap"]
+    g = np.random.default_rng(seed)
+    v = g.standard_normal(n)
+    mv = ctx.hss_matvec(_dev(v)).cpu().numpy()
+    mref = np.empty(n)
+    mref[perm] = ohss.matvec(H, v[perm])
+    assert _rel(mv, mref) <= 1e-12
+    lam = np.linalg.eigvalsh(ohss.densify(H))[0] if n <= 2048 else 0.0
+    beta = p["beta"]
+    if lam + beta <= 1e-3 * beta:
+        ctx.close()
+        pytest.skip("guard off and K~ + beta I not safely definite: the solve is not defined for this draw")
+    ctx.hss_ulv_factor(beta)
+    x = _dev(v)
+    ctx.hss_ulv_solve(x)
+    Fz = oulv.ulv_factor(H, beta)
+    xref = np.empty(n)
+    xref[perm] = oulv.ulv_solve(Fz, v[perm])
+    cond = (np.linalg.eigvalsh(ohss.densify(H))[-1] + beta) / (lam + beta)
+    assert _rel(x.cpu().numpy(), xref) <= max(1e-10, 1e-14 * cond), (cond,)
+    out = ctx.admm_svm_train(p["C"], beta, 12)
+    oref = oadmm.admm(lambda t: oulv.ulv_solve(Fz, t), p["y"][perm], p["C"], beta, 12)
+    if np.isfinite(oref["x"]).all() and np.abs(oref["x"]).max() < 1e8:     # (an indefinite K~ may blow the iteration up)
+        for key in ("x", "z", "mu"):
+            assert _rel(out[key].cpu().numpy()[perm], oref[key]) <= 1e-6, key
+    ctx.close()
