@@ -153,3 +153,38 @@ def test_import_rejects_inconsistent_generators():
         ctx.hss_import(F, ybad, 20.0, w.leaf, good)
     assert ctx.hss_import(F, y, 20.0, w.leaf, good) >= 0     # and the untouched arrays are accepted
     ctx.close()
+
+
+@pytest.mark.parametrize("seed,leaf,L", [(11, 16, 3), (12, 32, 2), (13, 16, 0), (14, 48, 3), (15, 64, 4)])
+def test_library_on_random_generators(seed, leaf, L):
+    """Generators that come from no kernel at all (random interpolative bases, ragged ranks down to 1 and up to
+    the node size, random coupling blocks): the library's mat-vec and ULV solve as pure HSS linear algebra."""
+    from gpu_helpers import export_from_oracle_hss
+    from test_oracle_random_generators import random_hss
+    H = random_hss(seed, leaf, L)
+    n = H.n
+    g = np.random.default_rng(seed)
+    F = g.standard_normal((n, 3))
+    y = np.where(g.random(n) < 0.5, -1.0, 1.0)
+    perm = g.permutation(n)
+    gen = export_from_oracle_hss(H, perm, 0.0)
+    ctx = binding.Context()
+    ctx.hss_import(_dev(F), _dev(y), 1.0, leaf, gen)
+    V = g.standard_normal((3, n))
+    for j in range(3):
+        mv = ctx.hss_matvec(_dev(V[j])).cpu().numpy()
+        ref = np.empty(n)
+        ref[perm] = ohss.matvec(H, V[j][perm])
+        assert _rel(mv, ref) <= 1e-12
+    for beta in (0.5, 7.0):
+        ctx.hss_ulv_factor(beta)
+        X = _dev(V)
+        ctx.hss_ulv_solve(X)
+        X = X.cpu().numpy()
+        A = ohss.densify(H) + beta * np.eye(n)
+        cond = np.linalg.cond(A)
+        for j in range(3):
+            ref = np.empty(n)
+            ref[perm] = np.linalg.solve(A, V[j][perm])
+            assert _rel(X[j], ref) <= max(1e-10, 1e-13 * cond), (beta, j, cond)
+    ctx.close()
