@@ -252,13 +252,26 @@ int admm_svm_train(hss_ctx* c, double C, double beta, int32_t maxit, double* x_o
 int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, double bias, double* dec) {
     if (!c || !G || !z || !dec || n_test < 0) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
+    if (n_test == 0) return HSS_OK;
     hipStream_t st = c->stream;
-    HSS_TRY(c->v_u.reserve(sizeof(double) * c->n));
-    HSS_TRY(c->v_e.reserve(sizeof(double) * c->n));
-    // zy in cluster-tree order
-    HSS_TRY(vec_gather(st, c->v_e.as<double>(), z, c->perm.as<int64_t>(), c->n));
-    HSS_TRY(vec_mul(st, c->v_u.as<double>(), c->v_e.as<double>(), c->yp.as<double>(), c->n));
-    HSS_TRY(decision_launch(st, c->Fp.as<double>(), c->v_u.as<double>(), c->n, G, n_test, c->r, c->r_pad, c->h, bias, dec));
+    // dec = K(G, F) (y .* z) + b is the sampling product with the test points as rows, the training points as
+    // columns and one "random" column y .* z: the same fused Gram + exp + contraction kernel, on a block of 128
+    // columns of which the first is used
+    const int sp = 128;
+    const int64_t nt_pad = round_up(n_test, 256);
+    DevBuf Gp, nug, Om, S;
+    HSS_TRY(Gp.reserve(sizeof(double) * nt_pad * c->r_pad));
+    HSS_TRY(nug.reserve(sizeof(double) * nt_pad));
+    HSS_TRY(Om.reserve(sizeof(double) * c->n_pad * sp));
+    HSS_TRY(S.reserve(sizeof(double) * nt_pad * sp));
+    HSS_TRY(gather_pad_rows_launch(st, G, nullptr, Gp.as<double>(), n_test, nt_pad, c->r, c->r_pad));
+    HSS_TRY(row_norms_launch(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->r_pad));
+    HSS_TRY(fill_launch(st, Om.as<double>(), c->n_pad * sp, 0.0));
+    HSS_TRY(zy_column(st, Om.as<double>(), sp, z, c->yp.as<double>(), c->perm.as<int64_t>(), c->n));
+    HSS_TRY(sample_launch_rect(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->Fp.as<double>(), c->nu.as<double>(),
+                               c->n_pad, Om.as<double>(), S.as<double>(), c->r_pad, sp, c->h));
+    HSS_TRY(decision_finish(st, dec, S.as<double>(), sp, bias, n_test));
+    HIP_TRY(hipStreamSynchronize(st));   // the temporaries are freed on return
     return HSS_OK;
 }
 

@@ -52,9 +52,12 @@ __device__ __forceinline__ double exp_nonpos(double x, const double (&c)[8], con
 // One workgroup of 8 wavefronts (WR x WC); every wavefront owns a 64 x (16*CT) block of S.
 // GP: Gram k-steps issued per contraction k-step; the feature dimension is padded to r_pad = 28 * GP.
 template <int WR, int WC, int CT, int GP>
-__global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ Fp, const double* __restrict__ nu,
+__global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ Fr, const double* __restrict__ nur,
+                                                      const double* __restrict__ Fp, const double* __restrict__ nu,
                                                       const double* __restrict__ Om, double* __restrict__ S,
                                                       int n_pad, int s_pad, double inv2h2) {
+    // rows of S: the points (Fr, nur), one workgroup per BMR of them; columns of K: the points (Fp, nu), n_pad of
+    // them.  The two sets are the same for the compression sample and differ for the label assignment.
     static_assert(WR * WC == 8, "8 wavefronts");
     constexpr int BMR = 64 * WR;           // rows of S per workgroup
     constexpr int LDK = BMR + 1;           // leading dimension of the K tile (j-major); odd: the exp results of 16 lanes
@@ -94,9 +97,9 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
     if (tid < 64) tab_s[tid] = exp2((double)tid * (1.0 / 64.0));
     for (int idx = tid; idx < BMR * RP; idx += 512) {
         int rr = idx / RP, cc = idx - rr * RP;
-        Fi_s[rr * LDF + cc] = Fp[(size_t)row0 * RP + idx];
+        Fi_s[rr * LDF + cc] = Fr[(size_t)row0 * RP + idx];
     }
-    for (int idx = tid; idx < BMR; idx += 512) nui_s[idx] = -nu[row0 + idx] * inv2h2;
+    for (int idx = tid; idx < BMR; idx += 512) nui_s[idx] = -nur[row0 + idx] * inv2h2;
     for (int b = 0; b < 2; ++b) {
         int jb = b < NJ ? b : NJ - 1;
         for (int idx = tid; idx < TILE; idx += 512) {
@@ -249,26 +252,26 @@ size_t sample_smem(int r_pad) {
 }
 
 template <int WR, int WC, int CT, int GP>
-int sample_go_g(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
-                int s_pad, double inv2h2) {
+int sample_go_g(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp, const double* nu,
+                const double* Om, double* S, int64_t n_pad, int s_pad, double inv2h2) {
     size_t smem = sample_smem<WR>(28 * GP);
     auto kern = sample_kernel<WR, WC, CT, GP>;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
-    dim3 grid((unsigned)(n_pad / (64 * WR)), (unsigned)(s_pad / (16 * CT * WC)));
-    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, Fp, nu, Om, S, (int)n_pad, s_pad, inv2h2);
+    dim3 grid((unsigned)(nr_pad / (64 * WR)), (unsigned)(s_pad / (16 * CT * WC)));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, Fr, nur, Fp, nu, Om, S, (int)n_pad, s_pad, inv2h2);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
 
 template <int WR, int WC, int CT>
-int sample_go(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
-              int r_pad, int s_pad, double inv2h2) {
+int sample_go(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp, const double* nu,
+              const double* Om, double* S, int64_t n_pad, int r_pad, int s_pad, double inv2h2) {
     switch (r_pad / 28) {
-        case 1: return sample_go_g<WR, WC, CT, 1>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 2: return sample_go_g<WR, WC, CT, 2>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 3: return sample_go_g<WR, WC, CT, 3>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 4: return sample_go_g<WR, WC, CT, 4>(st, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 1: return sample_go_g<WR, WC, CT, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 2: return sample_go_g<WR, WC, CT, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 3: return sample_go_g<WR, WC, CT, 3>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 4: return sample_go_g<WR, WC, CT, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
         default: return HSS_EUNSUPPORTED;
     }
 }
@@ -346,21 +349,29 @@ __global__ void omega_fill_kernel(double* __restrict__ Om, int64_t n, int64_t n_
 
 }  // namespace
 
-int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
-                  int r_pad, int s_pad, double h) {
-    if (n_pad % 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 || s_pad % 128 || s_pad < 128) return HSS_EUNSUPPORTED;
+// S (nr_pad x s_pad) = K(rows, cols) Om with rows = the points (Fr, nur), cols = the points (Fp, nu); Om is
+// n_pad x s_pad.  Both point sets are padded (rows to a multiple of 256, features to r_pad).
+int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                       const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int s_pad, double h) {
+    if (n_pad % 256 || nr_pad % 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 || s_pad % 128 || s_pad < 128)
+        return HSS_EUNSUPPORTED;
     const double inv2h2 = 1.0 / (2.0 * h * h);
     // Widest block of S per workgroup whose column span divides s_pad and whose LDS footprint fits:
     // 64 x 512, else 128 x 256 (64 x 256 when the feature tiles are too large), else 128 x 128 (64 x 128).
     const size_t lds_cap = 150 * 1024;
     const bool fit2 = sample_smem<2>(r_pad) <= lds_cap;
     if (sample_smem<1>(r_pad) > lds_cap) return HSS_EUNSUPPORTED;
-    if (s_pad % 512 == 0) return sample_go<1, 8, 4>(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
+    if (s_pad % 512 == 0) return sample_go<1, 8, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
     if (s_pad % 256 == 0)
-        return fit2 ? sample_go<2, 4, 4>(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
-                    : sample_go<1, 8, 2>(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
-    return fit2 ? sample_go<2, 4, 2>(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
-                : sample_go<1, 8, 1>(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
+        return fit2 ? sample_go<2, 4, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
+                    : sample_go<1, 8, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
+    return fit2 ? sample_go<2, 4, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
+                : sample_go<1, 8, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
+}
+
+int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
+                  int r_pad, int s_pad, double h) {
+    return sample_launch_rect(st, Fp, nu, n_pad, Fp, nu, n_pad, Om, S, r_pad, s_pad, h);
 }
 
 int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad) {

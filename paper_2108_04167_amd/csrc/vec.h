@@ -34,5 +34,5 @@ int vec_scatter_cols(hipStream_t st, double* dst, const double* src, const int64
 int margin_indicator(hipStream_t st, const double* z, double C, double* ebar, int64_t n);
 int bias_sums(hipStream_t st, const double* z, const double* y, const double* u, const double* ebar, int64_t n,
               double* partial_dev, double* out_dev);
-int decision_launch(hipStream_t st, const double* Fp, const double* zy, int64_t n, const double* G, int64_t n_test, int r,
-                    int r_pad, double h, double bias, double* dec);
+int zy_column(hipStream_t st, double* Om, int ld, const double* z, const double* yp, const int64_t* perm, int64_t n);
+int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double bias, int64_t n_test);

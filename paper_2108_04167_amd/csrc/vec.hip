@@ -202,48 +202,17 @@ __global__ void lanczos_update_kernel(double* __restrict__ w, const double* __re
     if (i < n) w[i] = w[i] - alpha * v[i] - beta * vp[i];
 }
 
-// Label assignment (Algorithm 3, last loop): dec_j = sum_i zy_i exp(-||f_i - g_j||^2 / (2h^2)) + b.
-// A workgroup owns 64 test points (tile in LDS) and walks over the training points 64 at a time; thread
-// (g, j) accumulates training points g, g+4, ... of each tile for test point j.
-__global__ __launch_bounds__(256) void decision_kernel(const double* __restrict__ Fp, const double* __restrict__ zy,
-                                                       int64_t n, const double* __restrict__ G, int64_t n_test, int r,
-                                                       int r_pad, double inv2h2, double bias, double* __restrict__ dec) {
-    extern __shared__ double sm[];
-    const int ldf = r_pad + 1;
-    double* Gs = sm;                  // 64 x ldf
-    double* Fs = sm + 64 * ldf;       // 64 x ldf
-    double* zs = Fs + 64 * ldf;       // 64
-    double* red = zs + 64;            // 4 x 64
-    const int tid = threadIdx.x;
-    const int j = tid & 63, g = tid >> 6;
-    const int64_t j0 = (int64_t)blockIdx.x * 64;
-    for (int idx = tid; idx < 64 * r_pad; idx += 256) {
-        int q = idx / r_pad, f = idx - q * r_pad;
-        Gs[q * ldf + f] = (j0 + q < n_test && f < r) ? G[(j0 + q) * r + f] : 0.0;
-    }
-    double acc = 0.0;
-    for (int64_t i0 = 0; i0 < n; i0 += 64) {
-        __syncthreads();
-        for (int idx = tid; idx < 64 * r_pad; idx += 256) {
-            int q = idx / r_pad, f = idx - q * r_pad;
-            Fs[q * ldf + f] = (i0 + q < n) ? Fp[(i0 + q) * r_pad + f] : 0.0;
-        }
-        if (tid < 64) zs[tid] = (i0 + tid < n) ? zy[i0 + tid] : 0.0;
-        __syncthreads();
-        for (int q = g; q < 64; q += 4) {
-            const double c = zs[q];
-            if (c == 0.0) continue;
-            double d2 = 0.0;
-            for (int f = 0; f < r_pad; ++f) {
-                double d = Fs[q * ldf + f] - Gs[j * ldf + f];
-                d2 += d * d;
-            }
-            acc += c * exp(-d2 * inv2h2);
-        }
-    }
-    red[g * 64 + j] = acc;
-    __syncthreads();
-    if (g == 0 && j0 + j < n_test) dec[j0 + j] = ((red[j] + red[64 + j]) + red[128 + j]) + red[192 + j] + bias;
+// Label assignment (Algorithm 3, last loop), the parts around the kernel product:
+// Om[i * ld] = y_i z_i (cluster-tree order; z in caller order), and dec_j = S[j * ld] + b.
+__global__ void zy_column_kernel(double* __restrict__ Om, int ld, const double* __restrict__ z, const double* __restrict__ yp,
+                                 const int64_t* __restrict__ perm, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) Om[i * ld] = yp[i] * z[perm[i]];
+}
+__global__ void decision_finish_kernel(double* __restrict__ dec, const double* __restrict__ S, int ld, double bias,
+                                       int64_t n_test) {
+    int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < n_test) dec[j] = S[j * ld] + bias;
 }
 
 }  // namespace
@@ -339,14 +308,13 @@ int bias_sums(hipStream_t st, const double* z, const double* y, const double* u,
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
-int decision_launch(hipStream_t st, const double* Fp, const double* zy, int64_t n, const double* G, int64_t n_test, int r,
-                    int r_pad, double h, double bias, double* dec) {
-    if (n_test <= 0) return HSS_OK;
-    size_t smem = sizeof(double) * (128 * (r_pad + 1) + 64 + 256);
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(decision_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem));
-    hipLaunchKernelGGL(decision_kernel, dim3((unsigned)((n_test + 63) / 64)), dim3(256), smem, st, Fp, zy, n, G, n_test, r,
-                       r_pad, 1.0 / (2.0 * h * h), bias, dec);
+int zy_column(hipStream_t st, double* Om, int ld, const double* z, const double* yp, const int64_t* perm, int64_t n) {
+    hipLaunchKernelGGL(zy_column_kernel, dim3(eb(n)), dim3(256), 0, st, Om, ld, z, yp, perm, n);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double bias, int64_t n_test) {
+    hipLaunchKernelGGL(decision_finish_kernel, dim3(eb(n_test)), dim3(256), 0, st, dec, S, ld, bias, n_test);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
