@@ -19,7 +19,7 @@ HBM_PEAK_GBS = 8000.0
 FP64_MFMA_PEAK_TFLOPS = 78.6
 # (workload, n) -> HBM bytes per launch (sample_kernel) / per solve (all solve_gemv_kernel launches of one solve),
 # read + written, from profiles/sample_kernel_cfg3_counters.txt and profiles/solve_gemv_kernel_cfg3_counters.txt.
-MEASURED_TRAFFIC_BYTES = {(3, 262144): {"sample_kernel": 5.802e11, "solve": 4.388e9}}
+MEASURED_TRAFFIC_BYTES = {(3, 262144): {"sample_kernel": 7.627e11, "solve": 4.388e9}}
 
 
 def cpu_baseline(cfg, n_small, maxit):
