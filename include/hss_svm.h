@@ -137,6 +137,13 @@ int admm_svm_train_multi(hss_ctx* ctx, const double* C_list, int32_t nC, double 
 int svm_decision(hss_ctx* ctx, const double* G_dev, int64_t n_test, const double* z_dev, double bias,
                  double* dec_out_dev);
 
+/* dst[0..n) = src[0..n): a plain streaming copy (16-byte accesses) on the context's stream, with exactly
+ * 8n bytes read and 8n written.  It is the measurement reference of this library: the bandwidth a trivial
+ * kernel reaches on the device at hand, and the known traffic that turns raw memory-counter readings into
+ * bytes (the roofline of the ULV solve, the operation of Sec. 2.1.1 that every iteration repeats, is quoted
+ * against both).  src, dst (dev, 16-byte aligned, not overlapping), n even and >= 2.  Asynchronous. */
+int hss_stream_copy(hss_ctx* ctx, const double* src_dev, double* dst_dev, int64_t n);
+
 typedef struct hss_stats_t {
     int64_t n, r, leaf, levels;        /* levels = L (leaves are level L, root level 0)                    */
     int64_t sample_width, rank_cap;

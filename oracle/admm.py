@@ -71,11 +71,15 @@ def margin_set(z, C):
     return (z > 0.0) & (z < C)
 
 
-def bias(z, y, C, kmatvec):
+def bias(z, y, C, kmatvec, M=None):
     """Averaged bias over the margin set with one kernel mat-vec (eq. 7 with the
     sign fixed by the margin identity).  kmatvec(v) = K v (or K~ v).
+    M: the margin set as a boolean mask; default {j : 0 < z_j < C}.  (A caller
+    comparing two nearly equal iterates passes one of the two sets to both, so
+    that an entry within rounding of a bound does not change the average.)
     Returns (b, |M|); b = 0 when M is empty."""
-    M = margin_set(z, C)
+    if M is None:
+        M = margin_set(z, C)
     cnt = int(M.sum())
     if cnt == 0:
         return 0.0, 0

@@ -46,6 +46,7 @@ ABI = {
     "admm_svm_train_multi": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_int32, C.c_double, C.c_int32, c_dp, c_dp,
                                        c_dp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "svm_decision": (C.c_int, [C.c_void_p, c_dp, C.c_int64, c_dp, C.c_double, c_dp]),
+    "hss_stream_copy": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64]),
     "hss_stats": (C.c_int, [C.c_void_p, C.POINTER(HssStats)]),
     "hss_export_sizes": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
     "hss_export": (C.c_int, [C.c_void_p, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, C.POINTER(C.c_double)]),
@@ -190,6 +191,11 @@ class Context:
         dec = torch.empty(G.shape[0], dtype=torch.float64, device=G.device)
         _check(_lib.svm_decision(self._h, _ptr(G), G.shape[0], _ptr(z), float(bias), _ptr(dec)), "svm_decision")
         return dec
+
+    def hss_stream_copy(self, src, dst):
+        _dev_f64(src, "src")
+        _dev_f64(dst, "dst", src.numel())
+        return _check(_lib.hss_stream_copy(self._h, _ptr(src), _ptr(dst), src.numel()), "hss_stream_copy")
 
     def hss_stats(self):
         st = HssStats()

@@ -1,4 +1,6 @@
-"""Builds libhsssvm.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds, in-tree with hipcc for gfx950 only: libhsssvm.so (the product: C ABI of include/hss_svm.h),
+libhsssvm_hooks.so (building-block entry points for the GPU unit tests, linked against the product library)
+and native/hss_bench_native (a C driver of the ABI for hardware-counter runs)."""
 from __future__ import annotations
 
 import os
@@ -10,6 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhsssvm.so")
+HOOKS_SRC = os.path.join(HERE, "csrc_test", "test_hooks.hip")
+HOOKS_LIB = os.path.join(HERE, "libhsssvm_hooks.so")
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -40,6 +44,11 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stdout}\n{res.stderr}")
+    # the unit tests' hooks: a library of their own that calls into the product library
+    cmd = [hipcc, *FLAGS, "-shared", HOOKS_SRC, "-o", HOOKS_LIB, "-L" + HERE, "-lhsssvm", "-Wl,-rpath,$ORIGIN"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"test hooks failed:\n{res.stdout}\n{res.stderr}")
     # stand-alone driver of the C ABI (for hardware-counter runs that must wrap a plain executable)
     drv = os.path.join(HERE, "native", "hss_bench_native")
     cmd = [hipcc, "-O2", "-std=c++17", os.path.join(HERE, "native", "hss_bench_native.cpp"), "-o", drv,

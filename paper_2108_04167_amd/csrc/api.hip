@@ -275,6 +275,12 @@ int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, d
     return HSS_OK;
 }
 
+int hss_stream_copy(hss_ctx* c, const double* src, double* dst, int64_t n) {
+    if (!c || !src || !dst || n < 2 || (n & 1)) return HSS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return HSS_EINVAL;
+    return stream_copy_launch(c->stream, src, dst, n);
+}
+
 int hss_stats(hss_ctx* c, hss_stats_t* o) {
     if (!c || !o) return HSS_EINVAL;
     memset(o, 0, sizeof(*o));

@@ -36,3 +36,4 @@ int bias_sums(hipStream_t st, const double* z, const double* y, const double* u,
               double* partial_dev, double* out_dev);
 int zy_column(hipStream_t st, double* Om, int ld, const double* z, const double* yp, const int64_t* perm, int64_t n);
 int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double bias, int64_t n_test);
+int stream_copy_launch(hipStream_t st, const double* src, double* dst, int64_t n);   // n even, 16-byte aligned

@@ -215,6 +215,13 @@ __global__ void decision_finish_kernel(double* __restrict__ dec, const double* _
     if (j < n_test) dec[j] = S[j * ld] + bias;
 }
 
+// dst = src, 16 bytes per lane and access, grid-stride: the plain streaming copy whose known traffic
+// calibrates bandwidth figures and the memory counters
+__global__ __launch_bounds__(256) void stream_copy_kernel(const double2* __restrict__ src, double2* __restrict__ dst,
+                                                          size_t n2) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n2; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 }  // namespace
 
 static unsigned eb(int64_t n) { return (unsigned)((n + 255) / 256); }
@@ -315,6 +322,12 @@ int zy_column(hipStream_t st, double* Om, int ld, const double* z, const double*
 }
 int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double bias, int64_t n_test) {
     hipLaunchKernelGGL(decision_finish_kernel, dim3(eb(n_test)), dim3(256), 0, st, dec, S, ld, bias, n_test);
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+int stream_copy_launch(hipStream_t st, const double* src, double* dst, int64_t n) {
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(8192), dim3(256), 0, st, reinterpret_cast<const double2*>(src),
+                       reinterpret_cast<double2*>(dst), (size_t)n / 2);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }

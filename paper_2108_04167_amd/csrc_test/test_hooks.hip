@@ -1,6 +1,8 @@
-// Internal entry points used only by the GPU unit tests of the building blocks (not part of the
-// C ABI in include/hss_svm.h).
-#include "common.h"
+// Entry points used only by the GPU unit tests of the building blocks.  They are built into a library of
+// their own (libhsssvm_hooks.so, linked against libhsssvm.so) so that the shipped library exports nothing
+// but the C ABI of include/hss_svm.h; declarations in test_hooks.h.
+#include "test_hooks.h"
+#include "../csrc/common.h"
 #include <algorithm>
 
 namespace {
@@ -12,22 +14,7 @@ __global__ void probe_mfma_kernel(const double* a, const double* b, double* d) {
 }
 }  // namespace
 
-__global__ __launch_bounds__(256) void plain_copy_kernel(const double2* __restrict__ src, double2* __restrict__ dst,
-                                                         size_t n2) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n2; i += (size_t)gridDim.x * 256) dst[i] = src[i];
-}
-
 extern "C" {
-
-// dst[0..n) = src[0..n) (n even, 16-byte aligned pointers): a plain streaming copy of known size, the
-// reference that turns the memory counters' raw readings into bytes.
-int hsx_plain_copy(void* stream, const double* src_dev, double* dst_dev, int64_t n) {
-    if (n <= 0 || (n & 1)) return HSS_EINVAL;
-    hipLaunchKernelGGL(plain_copy_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream, (const double2*)src_dev,
-                       (double2*)dst_dev, (size_t)n / 2);
-    HIP_TRY(hipGetLastError());
-    return HSS_OK;
-}
 
 // d[l*4+v] = accumulator register v of lane l after one 16x16x4 f64 MFMA with per-lane operands a[l], b[l].
 int hsx_probe_mfma(const double* a_dev, const double* b_dev, double* d_dev) {
@@ -62,9 +49,9 @@ int hsx_bgemm(void* stream, int nitems, const int32_t* dims_host, const int64_t*
 }  // extern "C"
 
 // ---- building blocks exercised by tests/test_gpu_blocks.py ----
-#include "dense.h"
-#include "levels.h"
-#include "rowid.h"
+#include "../csrc/dense.h"
+#include "../csrc/levels.h"
+#include "../csrc/rowid.h"
 
 extern "C" {
 
@@ -115,10 +102,12 @@ int hsx_chol(void* stream, int nmat, const int32_t* n_host, const int64_t* offs_
 }
 
 // Row interpolative decompositions of `nnodes` row blocks of A (rows x ld, ld a multiple of 128, <= 512);
-// block t = rows moff[t] .. moff[t+1].  Outputs: ranks (host), J (host, nnodes x kcap), U (device, tight
+// block t = rows moff[t] .. moff[t+1].  gram = 0: row-pivoted Gram-Schmidt on the rows (one launch per pivot
+// step); gram = 1: pivoted Cholesky of the blocks' Gram matrices A_t A_t^T (the form the compression uses for
+// relative thresholds of 3e-6 and above).  Outputs: ranks (host), J (host, nnodes x kcap), U (device, tight
 // msz_t x k_t blocks one after the other in node order; caller sizes it as rows x kcap).
 int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, const int64_t* moff_host, int32_t kcap,
-               double rel, double abs_tol, int32_t* ranks_host, int32_t* J_host, double* U_dev) {
+               double rel, double abs_tol, int32_t gram, int32_t* ranks_host, int32_t* J_host, double* U_dev) {
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = moff_host[nnodes];
     int maxm = 0;
@@ -140,8 +129,32 @@ int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, co
     ia.W = W.as<double>(); ia.ld = ld; ia.moff = moff.as<int64_t>(); ia.kcap = kcap; ia.kc = kcap; ia.rows_per_block = 32;
     ia.rel = rel; ia.abs_tol = abs_tol; ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>();
     ia.rk = rk.as<int>(); ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>();
-    HSS_TRY(id_init(st, ia, rows, nnodes, n0.as<double>()));
-    HSS_TRY(id_steps(st, ia, nnodes, maxm, n0.as<double>(), n1.as<double>()));
+    if (gram) {
+        DescArena ar;
+        HSS_TRY(ar.init(size_t(8) << 20));
+        DevBuf Gm, goffd;
+        std::vector<int64_t> goff(nnodes + 1, 0);
+        std::vector<GemmItem> gg(nnodes);
+        for (int t = 0; t < nnodes; ++t) {
+            const int64_t m = moff_host[t + 1] - moff_host[t];
+            goff[t + 1] = goff[t] + m * m;
+        }
+        HSS_TRY(Gm.reserve(sizeof(double) * std::max<int64_t>(goff[nnodes], 1)));
+        HSS_TRY(goffd.reserve(sizeof(int64_t) * (nnodes + 1)));
+        HIP_TRY(hipMemcpyAsync(goffd.p, goff.data(), sizeof(int64_t) * (nnodes + 1), hipMemcpyHostToDevice, st));
+        for (int t = 0; t < nnodes; ++t) {
+            const int m = (int)(moff_host[t + 1] - moff_host[t]);
+            const double* At = W.as<double>() + (size_t)moff_host[t] * ld;
+            gg[t] = GemmItem{At, At, Gm.as<double>() + goff[t], m, m, ld, ld, ld, m};
+        }
+        HSS_TRY(bgemm_host(st, ar, gg, false, true, 1.0, 0.0));
+        HIP_TRY(hipMemsetAsync(Lc.p, 0, sizeof(double) * rows * kcap, st));
+        HSS_TRY(id_chol(st, ia, nnodes, maxm, Gm.as<double>(), goffd.as<int64_t>()));
+        HIP_TRY(hipStreamSynchronize(st));   // the arena and the Gram matrices go out of scope
+    } else {
+        HSS_TRY(id_init(st, ia, rows, nnodes, n0.as<double>()));
+        HSS_TRY(id_steps(st, ia, nnodes, maxm, n0.as<double>(), n1.as<double>()));
+    }
     HIP_TRY(hipMemcpyAsync(ranks_host, rk.p, sizeof(int) * nnodes, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     std::vector<int64_t> koff(nnodes + 1, 0), uoff(nnodes + 1, 0);

@@ -4,7 +4,7 @@
 //
 //   hss_bench_native n r s leaf h maxit [nsolve]
 //
-// After the library calls it runs the library's plain_copy_kernel three times on 2^27 doubles (1 GiB read,
+// After the library calls it runs the library's hss_stream_copy three times on 2^27 doubles (1 GiB read,
 // 1 GiB written per launch): the reference that converts the memory counters' raw readings into bytes.
 // All device code lives in the library: the executable itself carries no kernel.
 #include <hip/hip_runtime.h>
@@ -18,7 +18,6 @@
 
 #include "../../include/hss_svm.h"
 
-extern "C" int hsx_plain_copy(void* stream, const double* src_dev, double* dst_dev, int64_t n);   // library test hook
 
 static uint64_t splitmix(uint64_t& s) {
     s += 0x9E3779B97F4A7C15ull;
@@ -91,7 +90,6 @@ int main(int argc, char** argv) {
            (long long)n, r, s, leaf, t1 - t0, st.t_sample_kernel, st.sample_flops / st.t_sample_kernel / 1e12, t2 - t1,
            (t3 - t2) / nsolve * 1e3, st.factor_bytes / ((t3 - t2) / nsolve) / 1e9, maxit, t4 - t3, bias, (long long)nm,
            st.delta);
-    hss_destroy(ctx);
     {
         const size_t nd = (size_t)1 << 27;
         double *a = nullptr, *b = nullptr;
@@ -100,13 +98,14 @@ int main(int argc, char** argv) {
         hipMemset(b, 0, nd * sizeof(double));
         hipDeviceSynchronize();
         double tc = now();
-        for (int i = 0; i < 3; ++i) CHECK(hsx_plain_copy(nullptr, a, b, (int64_t)nd));
+        for (int i = 0; i < 3; ++i) CHECK(hss_stream_copy(ctx, a, b, (int64_t)nd));
         if (hipDeviceSynchronize() != hipSuccess) return 1;
-        printf("plain_copy_kernel: %.1f GB/s (read + write, 3 launches of 2 x 1 GiB)\n",
+        printf("stream_copy_kernel: %.1f GB/s (read + write, 3 launches of 2 x 1 GiB)\n",
                3.0 * 2.0 * nd * sizeof(double) / (now() - tc) / 1e9);
         hipFree(a);
         hipFree(b);
     }
+    hss_destroy(ctx);
     hipFree(dF);
     hipFree(dy);
     hipFree(dx);

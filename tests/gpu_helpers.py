@@ -8,8 +8,17 @@ from oracle import hss as ohss
 from paper_2108_04167_amd import binding
 
 
+_hooks = None
+
+
 def lib():
-    return binding.load()
+    """The unit tests' hook library (building blocks of the product library, one call each)."""
+    global _hooks
+    if _hooks is None:
+        import os
+        binding.load()
+        _hooks = C.CDLL(os.path.join(os.path.dirname(binding.LIB_PATH), "libhsssvm_hooks.so"))
+    return _hooks
 
 
 def dev(a):

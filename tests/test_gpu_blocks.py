@@ -124,7 +124,7 @@ def test_batched_cholesky(L):
         assert np.allclose(Lc, np.linalg.cholesky(A), rtol=1e-11, atol=1e-12)
 
 
-def _row_id(L, blocks, ld, kcap, rel, abs_tol):
+def _row_id(L, blocks, ld, kcap, rel, abs_tol, gram=0):
     import torch
     from gpu_helpers import dev, hptr, ptr
     rows = sum(b.shape[0] for b in blocks)
@@ -139,8 +139,9 @@ def _row_id(L, blocks, ld, kcap, rel, abs_tol):
     J = np.zeros((nn, kcap), dtype=np.int32)
     U = torch.zeros(rows * kcap, dtype=torch.float64, device="cuda:0")
     L.hsx_row_id.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_double, C.c_double,
-                             C.c_void_p, C.c_void_p, C.c_void_p]
-    assert L.hsx_row_id(None, ptr(dev(A)), ld, nn, hptr(moff), kcap, rel, abs_tol, hptr(ranks), hptr(J), ptr(U)) == 0
+                             C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    assert L.hsx_row_id(None, ptr(dev(A)), ld, nn, hptr(moff), kcap, rel, abs_tol, gram, hptr(ranks), hptr(J),
+                        ptr(U)) == 0
     U = U.cpu().numpy()
     out, uo = [], 0
     for t, b in enumerate(blocks):
@@ -170,6 +171,47 @@ def test_row_id_ragged_blocks(L):
         err = np.linalg.norm(b - U @ b[J]) / np.linalg.norm(b)
         assert err <= 1e-7, (m, k, err)
         assert np.abs(U).max() <= 20.0
+
+
+def _decaying_blocks(rng, shapes, decay):
+    """Blocks with singular values decay^j (ragged sizes, more columns than the numerical rank)."""
+    blocks = []
+    for (m, cols) in shapes:
+        k = min(m, cols)
+        Qa, _ = np.linalg.qr(rng.standard_normal((m, k)))
+        Qb, _ = np.linalg.qr(rng.standard_normal((cols, k)))
+        blocks.append((Qa * decay ** np.arange(k)) @ Qb.T)
+    return blocks
+
+
+@pytest.mark.parametrize("rel", [1e-2, 1e-3, 1e-4, 3e-5])
+@pytest.mark.parametrize("gram", [1, 0])
+def test_row_id_meets_the_tolerance_in_both_forms(L, rel, gram):
+    """Truncation of a block to a relative threshold (end of Sec. 3.2) where the threshold, not the cap, stops
+    the decomposition: the form built on the Gram matrix (the one the compression runs for thresholds of 3e-6
+    and above, i.e. on every workload) and the Gram-Schmidt form against the oracle's pivoted Householder QR.
+    The first discarded pivot is the largest remaining row norm, so every row of A - U A[J] is at most the
+    threshold long; the bound asserted is twice that."""
+    from oracle import hss as ohss
+    rng = np.random.default_rng(11)
+    shapes = [(64, 128), (100, 128), (33, 100), (256, 128), (16, 64), (200, 128), (512, 256), (130, 256)]
+    for decay, ld in ((0.8, 256), (0.93, 256)):
+        blocks = _decaying_blocks(rng, shapes, decay)
+        kcap = 250
+        res = _row_id(L, blocks, ld, kcap, rel, 0.0, gram)
+        for (k, J, U), b in zip(res, blocks):
+            m = b.shape[0]
+            Jo, Uo = ohss.row_id(b, rel, 0.0, kcap)
+            assert abs(k - Jo.size) <= 2, (m, k, Jo.size)
+            assert len(set(J.tolist())) == k and J.min() >= 0 and J.max() < m
+            assert np.array_equal(U[J], np.eye(k))
+            r00 = np.linalg.norm(b, axis=1).max()                # the first pivot: the longest row
+            resid = np.linalg.norm(b - U @ b[J], axis=1).max()
+            assert resid <= 2.0 * rel * r00, (m, k, resid / r00)
+            # and as good as the oracle's decomposition of the same block
+            resid_o = np.linalg.norm(b - Uo @ b[Jo], axis=1).max()
+            assert resid <= max(3.0 * resid_o, rel * r00)
+            assert np.abs(U).max() <= 10.0
 
 
 def test_row_id_rank_cap_and_zero_block(L):

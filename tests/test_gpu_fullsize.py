@@ -1,11 +1,13 @@
 """Parity at the full workload sizes, in the launch configuration the benchmark times (GPU only).
 
-cfg2 (n = 65 536) and cfg3 (n = 262 144, the benchmark's workload): sampled rows of S = K Omega against the
-oracle, then the exported compressed matrix goes through the oracle's ULV factorization, solve and ADMM
-(same staging as tests/test_gpu_path.py).  cfg4 (n = 1 048 576) and cfg5 (n = 262 144, r = 90): the oracle
-cannot factor in test time, so the solve is checked through a property that holds at any size -- the
-residual of (K~ + delta I + beta I) x = b evaluated with the ORACLE's HSS mat-vec on the exported generators --
-plus the invariants of the ADMM iterates.
+cfg2 (n = 65 536), cfg3 (n = 262 144, the benchmark's workload), cfg5 (n = 262 144, r = 90) and cfg4
+(n = 1 048 576): sampled rows of S = K Omega against the oracle, then the exported compressed matrix goes through
+the oracle's ULV factorization, solve and a few ADMM iterations (same staging as tests/test_gpu_path.py; an oracle
+solve takes 0.25 ... 4 s at these sizes, which bounds the iteration count here).  The workloads' FULL iteration
+counts (500 / 500 / 300 / 300) run against the oracle on cuts of n = 16 384 points with the workload's own leaf
+size, sample width and parameters (workload 1 runs whole, 200 iterations, in tests/test_gpu_path.py).  cfg4 and
+cfg5 additionally: the residual of (K~ + delta I + beta I) x = b with the ORACLE's HSS mat-vec for every beta of
+the sweep, and the invariants of the ADMM iterates.  cfg2: the guard's shift against the oracle's.
 """
 import ctypes as C
 import time
@@ -64,16 +66,42 @@ def _check_sampled_rows(ctx, w, Om_dev, nrows, seed):
     del S
 
 
-def _full_oracle_parity(w, admm_iters):
+def _bias_and_labels(ctx, w, out, oref, H, perm, name, n_test=512):
+    """eq. (7) and the label loop of Algorithm 3: the oracle's formula on the library's iterate, and on the
+    oracle's iterate over the library's margin set; the flips between the two margin sets are reported."""
+    yp = w.y[perm]
+    kmv = lambda v: ohss.matvec(H, v)
+    z = out["z"].cpu().numpy()[perm]
+    M_lib = oadmm.margin_set(z, w.C)
+    flips = int((M_lib != oadmm.margin_set(oref["z"], w.C)).sum())
+    _say(f"{name}: margin set {int(M_lib.sum())} of {w.n}, flips vs oracle {flips}")
+    assert flips <= 1e-3 * w.n
+    b_own, cnt_own = oadmm.bias(z, yp, w.C, kmv)
+    assert out["n_margin"] == cnt_own
+    assert abs(out["bias"] - b_own) <= 1e-6 * max(1.0, abs(b_own))
+    b_cross, _ = oadmm.bias(oref["z"], yp, w.C, kmv, M=M_lib)
+    assert abs(out["bias"] - b_cross) <= 1e-6 * max(1.0, abs(b_cross))
+    if flips == 0:
+        b_ref, _ = oadmm.bias(oref["z"], yp, w.C, kmv)
+        assert abs(out["bias"] - b_ref) <= 1e-6 * max(1.0, abs(b_ref))
+    G = w.F_test[:n_test]
+    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
+    dec_ref = oadmm.decision(w.F[perm], yp, oref["z"], b_cross, G, w.h)
+    assert np.abs(dec - dec_ref).max() <= 1e-6 * max(1.0, np.abs(dec_ref).max())
+    assert abs(oadmm.accuracy(dec, w.y_test[:n_test]) - oadmm.accuracy(dec_ref, w.y_test[:n_test])) <= 0.1
+
+
+def _full_oracle_parity(w, admm_iters, check_guard=False, sample_rows=16):
     from gpu_helpers import oracle_hss_from_export
     ctx = binding.Context()
     ctx.hss_set_i64("sample_width", w.s)
     F, y = _dev(w.F), _dev(w.y)
-    Om = _library_omega(w.n, w.s)
-    _say(f"{w.name}: sampled rows of S")
-    _check_sampled_rows(ctx, w, Om, 16, 1)
-    del Om
-    _say("compress")
+    if sample_rows:
+        Om = _library_omega(w.n, w.s)
+        _say(f"{w.name}: sampled rows of S")
+        _check_sampled_rows(ctx, w, Om, sample_rows, 1)
+        del Om
+    _say(f"{w.name}: compress")
     rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)            # in-library Omega: the benchmark's path
     assert rc >= 0
     _say("export")
@@ -81,11 +109,17 @@ def _full_oracle_parity(w, admm_iters):
     perm = exp["perm"]
     _say("oracle tree")
     assert np.array_equal(perm, cluster_tree(w.F, w.leaf))
+    if check_guard:
+        _say("oracle guard")
+        d_or = ohss.psd_shift(oracle_hss_from_export(exp, with_shift=False))
+        _say(f"delta: library {exp['delta']:.6g}, oracle {d_or:.6g}")
+        assert d_or / 1.1 <= exp["delta"] <= 1.1 * d_or
     H = oracle_hss_from_export(exp)
     i = w.n // w.leaf // 3
     blk = slice(i * w.leaf, (i + 1) * w.leaf)
     Fp = w.F[perm]
     assert np.abs(exp["D"][i] - gaussian_kernel(Fp[blk], Fp[blk], w.h)).max() <= 1e-14
+    del exp
     # P2: ULV solve on the same compressed matrix
     ctx.hss_ulv_factor(w.beta)
     rng = np.random.default_rng(3)
@@ -105,7 +139,7 @@ def _full_oracle_parity(w, admm_iters):
     mref[perm] = ohss.matvec(H, b[perm])
     assert _rel(yv, mref) <= 1e-12
     # P3: ADMM on the same compressed matrix
-    _say("ADMM")
+    _say(f"ADMM, {admm_iters} iterations")
     out = ctx.admm_svm_train(w.C, w.beta, admm_iters)
     yp = w.y[perm]
     oref = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), yp, w.C, w.beta, admm_iters)
@@ -113,26 +147,49 @@ def _full_oracle_parity(w, admm_iters):
         got = out[key].cpu().numpy()[perm]
         assert _rel(got, oref[key]) <= 1e-6, (key, _rel(got, oref[key]))
     _say("bias / decision")
-    b_ref, cnt_ref = oadmm.bias(oref["z"], yp, w.C, lambda v: ohss.matvec(H, v))
-    if out["n_margin"] == cnt_ref:
-        assert abs(out["bias"] - b_ref) <= 1e-6 * max(1.0, abs(b_ref))
-    # label assignment on a slice of the test set
-    G = w.F_test[:512]
-    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
-    dec_ref = oadmm.decision(Fp, yp, oref["z"], out["bias"], G, w.h)
-    assert np.abs(dec - dec_ref).max() <= 1e-6 * max(1.0, np.abs(dec_ref).max())
-    assert abs(oadmm.accuracy(dec, w.y_test[:512]) - oadmm.accuracy(dec_ref, w.y_test[:512])) <= 0.1
+    _bias_and_labels(ctx, w, out, oref, H, perm, w.name)
     ctx.close()
 
 
 def test_cfg2_full_size_against_oracle():
-    _full_oracle_parity(synth.make_workload(2), admm_iters=25)
+    _full_oracle_parity(synth.make_workload(2), admm_iters=25, check_guard=True)
 
 
 def test_cfg3_full_size_against_oracle():
-    t0 = time.time()
     _full_oracle_parity(synth.make_workload(3), admm_iters=6)
-    print(f"cfg3 full-size parity took {time.time() - t0:.0f} s")
+
+
+def test_cfg5_full_size_against_oracle():
+    _full_oracle_parity(synth.make_workload(5), admm_iters=6)
+
+
+def test_cfg4_full_size_against_oracle():
+    _full_oracle_parity(synth.make_workload(4), admm_iters=2, sample_rows=4)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_iteration_count_on_a_cut(cfg):
+    """Algorithm 3 end to end with the workload's own iteration count: x, z, mu, bias and labels after
+    500 / 500 / 300 / 300 iterations against the oracle on the same compressed matrix (n = 16 384 points of
+    the workload's generator, its leaf size, sample width, tolerance, h, C, beta)."""
+    from gpu_helpers import oracle_hss_from_export
+    w = synth.make_workload(cfg, n=16384)
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", w.s)
+    rc = ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol)
+    assert rc >= 0
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    H = oracle_hss_from_export(exp)
+    _say(f"{w.name} cut: {w.maxit} iterations, delta {exp['delta']:.4g}")
+    out = ctx.admm_svm_train(w.C, w.beta, w.maxit)
+    Fz = oulv.ulv_factor(H, w.beta)
+    oref = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), w.y[perm], w.C, w.beta, w.maxit)
+    for key in ("x", "z", "mu"):
+        got = out[key].cpu().numpy()[perm]
+        assert _rel(got, oref[key]) <= 1e-6, (key, _rel(got, oref[key]))
+    _bias_and_labels(ctx, w, out, oref, H, perm, w.name + " cut", n_test=2048)
+    ctx.close()
 
 
 def _property_parity(w, admm_iters, sweep=False):
@@ -173,10 +230,6 @@ def _property_parity(w, admm_iters, sweep=False):
     beta = betas[-1]
     muk = mu + beta * (xg - zg)
     assert np.abs(zg - np.clip(xg - muk / beta, 0.0, w.C)).max() <= 1e-12 * max(1.0, np.abs(xg).max())
-    # bias from the library's own iterate with the oracle's formula and mat-vec
-    b_own, cnt_own = oadmm.bias(zg[perm], w.y[perm], w.C, lambda v: ohss.matvec(H, v))
-    assert out["n_margin"] == cnt_own
-    assert abs(out["bias"] - b_own) <= 1e-6 * max(1.0, abs(b_own))
     assert st["rank_max"] <= st["rank_cap"]
     ctx.close()
 

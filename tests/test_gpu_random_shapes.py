@@ -75,6 +75,18 @@ def test_random_problem(seed):
     mref = np.empty(n)
     mref[perm] = ohss.matvec(H, v[perm])
     assert _rel(mv, mref) <= 1e-12
+    # reconstruction against the dense kernel: as good as the oracle's compression of the same sample, and
+    # within the tolerance when no node was cut by the cap and the sample is at least 10 columns wider than
+    # the largest rank (oversampling, end of Sec. 3.2)
+    Fp = p["F"][perm]
+    K = gaussian_kernel(Fp, Fp, p["h"])
+    Kt = ohss.densify(oracle_hss_from_export(exp, with_shift=False))
+    err = np.linalg.norm(K - Kt) / np.linalg.norm(K)
+    Ho = ohss.compress(Fp, p["h"], p["leaf"], p["Om"][perm], p["tol"] / 10.0, 1e-8, st["rank_cap"])
+    err_or = np.linalg.norm(K - ohss.densify(Ho)) / np.linalg.norm(K)
+    assert err <= max(p["tol"], 1.5 * err_or, 1e-9), (err, err_or)
+    if n > p["leaf"] and st["nodes_at_cap"] == 0 and exp["ranks"].max() <= p["s"] - 10:
+        assert err <= max(p["tol"], 1e-9), (err, p["tol"])
     lam = np.linalg.eigvalsh(ohss.densify(H))[0] if n <= 2048 else 0.0
     beta = p["beta"]
     if lam + beta <= 1e-3 * beta:

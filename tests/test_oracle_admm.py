@@ -15,25 +15,31 @@ def _problem(n, r, h, seed, noise=0.3):
 
 
 def test_x_update_solves_the_bordered_kkt_system():
-    # Sec. 2.1: [[Y K_beta Y, -y], [-y^T, 0]] [x; lambda] = [q; 0]
-    n, beta = 96, 0.8
+    """Sec. 2.1: x^{k+1} is the x-part of  [[Y K_beta Y, -y], [-y^T, 0]] [x; lambda] = [q^k; 0]  with
+    q^k = e + mu^k + beta z^k.  The oracle's own trajectory is used: k iterations give (z^k, mu^k), k + 1
+    iterations give x^{k+1}; the bordered system is solved densely, with no use of the closed form."""
+    n, beta, C = 96, 0.8, 0.6
     F, y, K, rng = _problem(n, 3, 1.5, 0)
     Kb = K + beta * np.eye(n)
-    mu = rng.standard_normal(n)
-    z = rng.uniform(0, 1, n)
-    q = 1.0 + mu + beta * z
     big = np.zeros((n + 1, n + 1))
     big[:n, :n] = (y[:, None] * Kb) * y[None, :]
     big[:n, n] = -y
     big[n, :n] = -y
-    ref = np.linalg.solve(big, np.concatenate([q, [0.0]]))[:n]
-    # one oracle iteration started from (z, mu) reproduces x^{k+1}
-    wbar = np.linalg.solve(Kb, np.ones(n))
-    w1 = wbar.sum()
-    w = y * wbar
-    x = y * np.linalg.solve(Kb, y * q) - (w @ q / w1) * w
-    assert np.allclose(x, ref, rtol=1e-11, atol=1e-12)
-    assert abs(y @ x) < 1e-11
+    for k in (0, 1, 2, 7, 30):
+        prev = admm.admm_dense(K, y, C, beta, k)
+        nxt = admm.admm_dense(K, y, C, beta, k + 1)
+        q = 1.0 + prev["mu"] + beta * prev["z"]
+        ref = np.linalg.solve(big, np.concatenate([q, [0.0]]))[:n]
+        assert np.allclose(nxt["x"], ref, rtol=1e-10, atol=1e-11), k
+        assert abs(y @ nxt["x"]) < 1e-10
+        # the other two updates of Algorithm 2, from the same pair of states
+        assert np.array_equal(nxt["z"], np.clip(nxt["x"] - prev["mu"] / beta, 0.0, C))          # eq. (6)
+        assert np.allclose(nxt["mu"], prev["mu"] - beta * (nxt["x"] - nxt["z"]), rtol=0, atol=1e-15)
+    assert np.abs(prev["mu"]).max() > 1e-3 and (prev["z"] > 0).any()     # the states fed back are not trivial
+    # a trajectory that ignored the feedback of z and mu (the misprint in Algorithm 3) would fail this
+    stale = 1.0 + 0.0 * prev["mu"]
+    bad = np.linalg.solve(big, np.concatenate([stale, [0.0]]))[:n]
+    assert not np.allclose(nxt["x"], bad, rtol=1e-3, atol=1e-4)
 
 
 def test_first_iteration_matches_hand_formula_and_invariants():
