@@ -81,6 +81,18 @@ int hss_set_f64(hss_ctx* ctx, const char* key, double v);
 int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h,
                       const double* Omega_dev, int32_t s, double* S_out_dev);
 
+/* hss_kernel_sample for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result as
+ * hss_kernel_sample, but the padded work copies live in a fixed 12.1 MB device array inside the library
+ * (one per GPU, held until the process ends) and the call makes no hipMalloc / hipFree and does not
+ * synchronise: it is asynchronous on the context's stream.  Limits: n <= 4096, r <= 96, s <= 128;
+ * larger sizes return HSS_EUNSUPPORTED and write nothing.  All calls on one GPU share the array: calls
+ * that overlap in time on one GPU (other streams, other threads, other contexts) race, and S_out of a call
+ * is final only when its stream has reached the end of that call.  The array's device address is looked up
+ * when the first context is created on a GPU (or, failing that, by the first call on that GPU). */
+int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h,
+                              const double* Omega_dev, int32_t s, double* S_out_dev);
+
 /* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection on the
  * coordinate of largest variance), random sampling S = K Omega, interpolative decompositions level by
  * level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,

@@ -34,6 +34,7 @@ ABI = {
     "hss_set_i64": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int64]),
     "hss_set_f64": (C.c_int, [C.c_void_p, C.c_char_p, C.c_double]),
     "hss_kernel_sample": (C.c_int, [C.c_void_p, c_dp, C.c_int64, C.c_int32, C.c_double, c_dp, C.c_int32, c_dp]),
+    "hss_kernel_sample_noalloc": (C.c_int, [C.c_void_p, c_dp, C.c_int64, C.c_int32, C.c_double, c_dp, C.c_int32, c_dp]),
     "hss_compress": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32, C.c_double]),
     "hss_compress_with_samples": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32,
                                             C.c_double, c_dp, C.c_int32]),
@@ -137,6 +138,16 @@ class Context:
         S = torch.empty((n, s), dtype=torch.float64, device=F.device)
         _check(_lib.hss_kernel_sample(self._h, _ptr(F), n, r, float(h), _ptr(Omega), s, _ptr(S)), "hss_kernel_sample")
         return S
+
+    def hss_kernel_sample_noalloc(self, F, h, Omega, S_out):
+        """Allocation-free variant: the caller brings S_out (n x s); asynchronous on the context's stream."""
+        n, r = F.shape
+        s = Omega.shape[1]
+        _dev_f64(F, "F")
+        _dev_f64(Omega, "Omega", n * s)
+        _dev_f64(S_out, "S_out", n * s)
+        return _check(_lib.hss_kernel_sample_noalloc(self._h, _ptr(F), n, r, float(h), _ptr(Omega), s, _ptr(S_out)),
+                      "hss_kernel_sample_noalloc")
 
     def hss_compress(self, F, y, h, leaf, tol, Omega=None):
         n, r = F.shape

@@ -25,6 +25,10 @@ int hss_create(hss_ctx** out, void* hip_stream) {
     hss_ctx* c = new (std::nothrow) hss_ctx();
     if (!c) return HSS_ENOMEM;
     c->stream = (hipStream_t)hip_stream;
+    // set-up of the allocation-free entry point: the scratch array's address on this device.  A failure here
+    // is not one of hss_create (the entry point asks again and reports it).
+    double* unused = nullptr;
+    (void)noalloc_scratch_for_current_device(&unused);
     *out = c;
     return HSS_OK;
 }

@@ -82,6 +82,8 @@ struct hss_ctx {
 
 int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int64_t* perm_dev, int* bad_dev);
 
+// noalloc.hip: device address of the library's fixed scratch array on the current device
+int noalloc_scratch_for_current_device(double** out);
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
                       const double* Omega, int s_in);
