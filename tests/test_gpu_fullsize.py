@@ -91,7 +91,9 @@ def _bias_and_labels(ctx, w, out, oref, H, perm, name, n_test=512):
     assert abs(oadmm.accuracy(dec, w.y_test[:n_test]) - oadmm.accuracy(dec_ref, w.y_test[:n_test])) <= 0.1
 
 
-def _full_oracle_parity(w, admm_iters, check_guard=False, sample_rows=16):
+def _stage_compress(w, check_guard=False, sample_rows=16):
+    """Sampled rows of S, compression with the in-library Omega (the benchmark's path), export, tree and one
+    leaf block against the oracle.  Returns the state the later stages work on."""
     from gpu_helpers import oracle_hss_from_export
     ctx = binding.Context()
     ctx.hss_set_i64("sample_width", w.s)
@@ -102,7 +104,7 @@ def _full_oracle_parity(w, admm_iters, check_guard=False, sample_rows=16):
         _check_sampled_rows(ctx, w, Om, sample_rows, 1)
         del Om
     _say(f"{w.name}: compress")
-    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)            # in-library Omega: the benchmark's path
+    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)
     assert rc >= 0
     _say("export")
     exp = ctx.hss_export()
@@ -119,8 +121,12 @@ def _full_oracle_parity(w, admm_iters, check_guard=False, sample_rows=16):
     blk = slice(i * w.leaf, (i + 1) * w.leaf)
     Fp = w.F[perm]
     assert np.abs(exp["D"][i] - gaussian_kernel(Fp[blk], Fp[blk], w.h)).max() <= 1e-14
-    del exp
-    # P2: ULV solve on the same compressed matrix
+    return {"w": w, "ctx": ctx, "H": H, "perm": perm, "stats": ctx.hss_stats()}
+
+
+def _stage_solve(st):
+    """P2: ULV solve and mat-vec on the same compressed matrix."""
+    w, ctx, H, perm = st["w"], st["ctx"], st["H"], st["perm"]
     ctx.hss_ulv_factor(w.beta)
     rng = np.random.default_rng(3)
     b = rng.standard_normal(w.n)
@@ -128,27 +134,35 @@ def _full_oracle_parity(w, admm_iters, check_guard=False, sample_rows=16):
     ctx.hss_ulv_solve(x)
     x = x.cpu().numpy()
     _say("oracle ULV factor")
-    Fz = oulv.ulv_factor(H, w.beta)
+    st["Fz"] = Fz = oulv.ulv_factor(H, w.beta)
     _say("oracle ULV solve")
     ref = np.empty(w.n)
     ref[perm] = oulv.ulv_solve(Fz, b[perm])
     assert _rel(x, ref) <= 1e-10, _rel(x, ref)
-    # mat-vec
     yv = ctx.hss_matvec(_dev(b)).cpu().numpy()
     mref = np.empty(w.n)
     mref[perm] = ohss.matvec(H, b[perm])
     assert _rel(yv, mref) <= 1e-12
-    # P3: ADMM on the same compressed matrix
+
+
+def _stage_admm(st, admm_iters):
+    """P3: ADMM, bias and labels on the same compressed matrix."""
+    w, ctx, H, perm, Fz = st["w"], st["ctx"], st["H"], st["perm"], st["Fz"]
     _say(f"ADMM, {admm_iters} iterations")
     out = ctx.admm_svm_train(w.C, w.beta, admm_iters)
-    yp = w.y[perm]
-    oref = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), yp, w.C, w.beta, admm_iters)
+    oref = oadmm.admm(lambda v: oulv.ulv_solve(Fz, v), w.y[perm], w.C, w.beta, admm_iters)
     for key in ("x", "z", "mu"):
         got = out[key].cpu().numpy()[perm]
         assert _rel(got, oref[key]) <= 1e-6, (key, _rel(got, oref[key]))
     _say("bias / decision")
     _bias_and_labels(ctx, w, out, oref, H, perm, w.name)
-    ctx.close()
+
+
+def _full_oracle_parity(w, admm_iters, check_guard=False):
+    st = _stage_compress(w, check_guard)
+    _stage_solve(st)
+    _stage_admm(st, admm_iters)
+    st["ctx"].close()
 
 
 def test_cfg2_full_size_against_oracle():
@@ -163,8 +177,31 @@ def test_cfg5_full_size_against_oracle():
     _full_oracle_parity(synth.make_workload(5), admm_iters=6)
 
 
-def test_cfg4_full_size_against_oracle():
-    _full_oracle_parity(synth.make_workload(4), admm_iters=2, sample_rows=4)
+# Workload 4 (n = 1 048 576) in stages of its own, so that no single test is silent for minutes: generating
+# and compressing, the oracle's factorization (80 s), the iterations, the properties.
+@pytest.fixture(scope="module")
+def cfg4_state():
+    st = {}
+    yield st
+    if "ctx" in st:
+        st["ctx"].close()
+    st.clear()
+
+
+def test_cfg4_full_size_compression_against_oracle(cfg4_state):
+    cfg4_state.update(_stage_compress(synth.make_workload(4), sample_rows=4))
+
+
+def test_cfg4_full_size_ulv_solve_against_oracle(cfg4_state):
+    _stage_solve(cfg4_state)
+
+
+def test_cfg4_full_size_admm_against_oracle(cfg4_state):
+    _stage_admm(cfg4_state, admm_iters=2)
+
+
+def test_cfg4_full_size_properties(cfg4_state):
+    _property_parity(cfg4_state["w"], admm_iters=20, state=cfg4_state)
 
 
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
@@ -192,20 +229,23 @@ def test_full_iteration_count_on_a_cut(cfg):
     ctx.close()
 
 
-def _property_parity(w, admm_iters, sweep=False):
+def _property_parity(w, admm_iters, sweep=False, state=None):
     from gpu_helpers import oracle_hss_from_export
-    ctx = binding.Context()
-    ctx.hss_set_i64("sample_width", w.s)
-    F, y = _dev(w.F), _dev(w.y)
-    _say(f"{w.name}: compress")
-    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)
-    assert rc >= 0
-    st = ctx.hss_stats()
-    _say("export")
-    exp = ctx.hss_export()
-    perm = exp["perm"]
-    H = oracle_hss_from_export(exp)
-    del exp
+    if state is None:
+        ctx = binding.Context()
+        ctx.hss_set_i64("sample_width", w.s)
+        F, y = _dev(w.F), _dev(w.y)
+        _say(f"{w.name}: compress")
+        rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)
+        assert rc >= 0
+        st = ctx.hss_stats()
+        _say("export")
+        exp = ctx.hss_export()
+        perm = exp["perm"]
+        H = oracle_hss_from_export(exp)
+        del exp
+    else:
+        ctx, H, perm, st = state["ctx"], state["H"], state["perm"], state["stats"]
     rng = np.random.default_rng(5)
     b = rng.standard_normal(w.n)
     betas = w.beta_grid if sweep else (w.beta,)
@@ -231,12 +271,9 @@ def _property_parity(w, admm_iters, sweep=False):
     muk = mu + beta * (xg - zg)
     assert np.abs(zg - np.clip(xg - muk / beta, 0.0, w.C)).max() <= 1e-12 * max(1.0, np.abs(xg).max())
     assert st["rank_max"] <= st["rank_cap"]
-    ctx.close()
+    if state is None:
+        ctx.close()
 
 
 def test_cfg5_full_size_properties_and_beta_sweep():
     _property_parity(synth.make_workload(5), admm_iters=30, sweep=True)
-
-
-def test_cfg4_full_size_properties():
-    _property_parity(synth.make_workload(4), admm_iters=20)
