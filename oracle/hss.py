@@ -23,9 +23,12 @@ Nodes are numbered in heap order: root 0, children of t are 2t+1 and 2t+2; the
 leaves are the last 2^L nodes, left to right.
 
 Which rows an ID picks (and so the ranks) is not unique: "parity unpinned".
-What is pinned (tests/test_oracle_hss.py): reconstruction error <= tolerance
+What is pinned (tests/test_oracle_hss_ulv.py): reconstruction error <= tolerance
 against the dense kernel, exactness when the sample is wide and the tolerance
-tiny, the rank-one limit, densify/mat-vec agreement.
+tiny, the rank-one limit, densify/mat-vec agreement; for the adaptive width:
+identity with the fixed-width construction when nothing is cut, the tolerance
+met against the dense kernel where the first width alone fails it, and the
+width trajectory on a case with known block ranks.
 """
 import numpy as np
 import scipy.linalg as sla
@@ -151,6 +154,86 @@ def compress(Fp, h, leaf, Omega, rel_tol, abs_tol=0.0, kmax=None, S=None):
             Sred[t] = St[J]
             Ored[t] = U.T @ Ot
     return H
+
+
+def compress_adaptive(Fp, h, leaf, Omega, rel_tol, abs_tol=0.0, s0=None, step=128, oversample=None, kmax=None,
+                      S=None):
+    """The same construction with an adaptive sample width (oversampling and per-block
+    truncation to the tolerance, end of Sec. 3.2): the decompositions of a level first
+    see only the leading `width` columns of the sample; while some node of the level is
+    cut by the sample's rank cap (and not by the tolerance) and columns are left, the
+    width grows by `step` and the cut nodes -- only those -- are decomposed again from
+    the wider sample.  The width never shrinks on the way up the tree.
+
+    Omega (n, s) holds ALL columns that may ever be used; s0 is the first width
+    (default s: no adaptivity, identical to `compress`).  Rank cap at width c:
+    c - p with p = `oversample` (default c // 2), never above `kmax` (default: the
+    cap at the full width s).
+
+    A column of S~_t = S_t(J_t, :) or Om~_t = U_t^T Om_t depends on the same column
+    of S and Omega only, so using "the first c columns" of quantities computed at
+    full width equals computing the new columns when the width grows.
+
+    Returns (H, info): info["width"] = final width, info["level_width"][l] = width
+    in use when level l was finished, info["redone"] = number of node
+    decompositions repeated, info["nodes_at_cap"] = nodes still cut by a cap.
+    """
+    Fp = np.asarray(Fp, dtype=np.float64)
+    n = Fp.shape[0]
+    s = Omega.shape[1]
+    width = s if s0 is None else min(int(s0), s)
+    cap_at = lambda c: c - (c // 2 if oversample is None else int(oversample))
+    kfinal = cap_at(s) if kmax is None else int(kmax)
+    H = HSS(n, leaf)
+    if S is None:
+        S = sample(Fp, Omega, h)
+    Sred = [None] * H.nnodes
+    Ored = [None] * H.nnodes
+    fl = H.first_leaf()
+    info = {"level_width": {}, "redone": 0, "nodes_at_cap": 0}
+    for l in range(H.L, -1, -1):
+        St, Ot, idx = {}, {}, {}
+        for t in H.level_nodes(l):
+            if H.is_leaf(t):
+                i = t - fl
+                rows = np.arange(i * leaf, (i + 1) * leaf)
+                H.D[i] = gaussian_kernel(Fp[rows], Fp[rows], h)
+                St[t] = S[rows] - H.D[i] @ Omega[rows]
+                Ot[t] = Omega[rows]
+                idx[t] = rows
+            else:
+                a, b = 2 * t + 1, 2 * t + 2
+                H.B[t] = gaussian_kernel(Fp[H.skel[a]], Fp[H.skel[b]], h)
+                St[t] = np.vstack([Sred[a] - H.B[t] @ Ored[b], Sred[b] - H.B[t].T @ Ored[a]])
+                Ot[t] = np.vstack([Ored[a], Ored[b]])
+                idx[t] = np.concatenate([H.skel[a], H.skel[b]])
+                Sred[a] = Sred[b] = Ored[a] = Ored[b] = None
+        if l == 0:
+            break
+        todo = list(H.level_nodes(l))
+        while True:
+            cap = min(cap_at(width), kfinal)
+            if cap < 1:
+                raise ValueError("rank cap below 1")
+            cut = []
+            for t in todo:
+                J, U = row_id(St[t][:, :width], rel_tol, abs_tol, cap)
+                H.J[t], H.U[t] = J, U
+                if J.size == cap and J.size < St[t].shape[0]:
+                    cut.append(t)
+            if not cut or width >= s or cap >= kfinal:
+                info["nodes_at_cap"] += len(cut)
+                break
+            width = min(s, width + int(step))
+            todo = cut
+            info["redone"] += len(cut)
+        info["level_width"][l] = width
+        for t in H.level_nodes(l):
+            H.skel[t] = idx[t][H.J[t]]
+            Sred[t] = St[t][H.J[t]]
+            Ored[t] = H.U[t].T @ Ot[t]
+    info["width"] = width
+    return H, info
 
 
 def nested_basis(H, t):

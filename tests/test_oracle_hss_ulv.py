@@ -189,3 +189,70 @@ def test_psd_shift_restores_definiteness_and_is_zero_when_not_needed():
     Fp, Om, H2, _ = _compress(512, 2, 0.05, 32, 128, 1e-8, kmax=118)
     assert np.linalg.eigvalsh(hss.densify(H2))[0] > 0
     assert hss.psd_shift(H2) == 0.0
+
+
+# ---- adaptive sample width (oversampling / truncation to the tolerance, end of Sec. 3.2) ----
+
+def _adaptive_case(n, r, h, leaf, s, seed=0):
+    F, rng = _points(n, r, seed)
+    perm = cluster_tree(F, leaf)
+    Fp = F[perm]
+    Om = rng.standard_normal((n, s))
+    return Fp, Om, gaussian_kernel(Fp, Fp, h)
+
+
+def test_adaptive_equals_fixed_width_when_it_starts_at_the_full_width():
+    Fp, Om, K = _adaptive_case(512, 3, 1.5, 32, 96)
+    H0 = hss.compress(Fp, 1.5, 32, Om, 1e-5, 0.0, 96 - 48)
+    H1, info = hss.compress_adaptive(Fp, 1.5, 32, Om, 1e-5, 0.0)
+    assert info["width"] == 96 and info["redone"] == 0
+    assert np.array_equal(H0.ranks(), H1.ranks())
+    assert np.array_equal(hss.densify(H0), hss.densify(H1))
+    # ... and when the first width is already enough (nothing is cut), the extra columns are never looked at
+    H2, info2 = hss.compress_adaptive(Fp, 1.5, 32, Om, 1e-2, 0.0, s0=64, step=16, oversample=10)
+    H3 = hss.compress(Fp, 1.5, 32, Om[:, :64], 1e-2, 0.0, 54)
+    assert info2["width"] == 64 and info2["redone"] == 0 and info2["nodes_at_cap"] == 0
+    assert np.array_equal(hss.densify(H2), hss.densify(H3))
+
+
+def test_adaptive_width_meets_the_tolerance_where_the_first_width_cannot():
+    n, r, h, leaf, tol = 1024, 2, 1.0, 32, 1e-6
+    Fp, Om, K = _adaptive_case(n, r, h, leaf, 256, seed=3)
+    nrm = np.linalg.norm(K)
+    # first width alone: every upper node is cut by the cap, the tolerance is missed by orders of magnitude
+    Hf = hss.compress(Fp, h, leaf, Om[:, :32], tol / 10.0, 0.0, 22)
+    err_fixed = np.linalg.norm(K - hss.densify(Hf)) / nrm
+    assert err_fixed > 100 * tol
+    Ha, info = hss.compress_adaptive(Fp, h, leaf, Om, tol / 10.0, 0.0, s0=32, step=32, oversample=10)
+    err = np.linalg.norm(K - hss.densify(Ha)) / nrm
+    assert info["nodes_at_cap"] == 0 and info["redone"] > 0
+    assert err <= tol, (err, info)
+    assert 32 < info["width"] < 256                      # it grew, and stopped before using every column
+    assert Ha.ranks().max() < info["width"] - 10         # every rank is below the cap of the final width
+    widths = [info["level_width"][l] for l in range(Ha.L, 0, -1)]
+    assert widths == sorted(widths)                      # never shrinks on the way up
+    for i in range(n // leaf):
+        blk = slice(i * leaf, (i + 1) * leaf)
+        assert np.array_equal(hss.densify(Ha)[blk, blk], K[blk, blk])
+
+
+def test_adaptive_width_trajectory_on_known_ranks():
+    """h -> infinity: K = e e^T up to 1e-14, every block has rank one; with oversampling p = 3 a first width of
+    4 (cap 1) cuts every node although its rank IS one (a cap that is reached counts as a cut), one step to
+    width 6 (cap 3) settles it: all ranks 1, exactly one widening, at the leaf level only."""
+    Fp, Om, K = _adaptive_case(256, 3, 1e7, 32, 12)
+    H, info = hss.compress_adaptive(Fp, 1e7, 32, Om, 1e-8, 0.0, s0=4, step=2, oversample=3)
+    assert np.all(H.ranks()[1:] == 1)
+    assert info["width"] == 6 and info["redone"] == 8 and info["nodes_at_cap"] == 0
+    assert info["level_width"] == {3: 6, 2: 6, 1: 6}
+    assert np.allclose(hss.densify(H), 1.0, atol=1e-10)
+
+
+def test_adaptive_width_stops_at_the_last_column_and_reports_the_cut():
+    Fp, Om, K = _adaptive_case(512, 6, 1.0, 32, 64, seed=5)      # ranks far above what 64 columns can show
+    H, info = hss.compress_adaptive(Fp, 1.0, 32, Om, 1e-9, 0.0, s0=32, step=16)
+    assert info["width"] == 64 and info["nodes_at_cap"] > 0
+    assert H.ranks().max() == 32                                   # cap at the full width: 64 - 64 // 2
+    # identical to the fixed-width construction at the full width for the nodes of the last level decomposed
+    Hf = hss.compress(Fp, 1.0, 32, Om, 1e-9, 0.0, 32)
+    assert np.array_equal(H.ranks(), Hf.ranks())
