@@ -67,6 +67,16 @@ void hss_destroy(hss_ctx* ctx);
  *                           level by level)                                    (oversampling, end of Sec. 3.2)
  *        "max_rank"         explicit rank cap per node (default 0 = s - p)
  *        "seed"             seed of the counter-based generator that draws Omega (default 0)
+        "adaptive_start"   s0 > 0: adaptive sample width (oversampling / truncation of every block to the
+                           tolerance, end of Sec. 3.2).  The decompositions of a tree level first see the leading
+                           s0 columns of the sample; while a node of the level is cut by the sample's rank cap
+                           (w - p at width w, p = "oversample", default w/2) rather than by the tolerance, and
+                           columns are left, "adaptive_step" more columns of Omega are sampled (for all rows,
+                           and carried up through the finished levels) and the cut nodes -- only those -- are
+                           decomposed again.  "sample_width" (or the width of a caller's Omega) is then the
+                           LARGEST width, and the final rank cap is min("max_rank", s - p(s)).  s0, the step and
+                           s must be multiples of 128.  Default 0: off, all s columns are sampled at once.
+        "adaptive_step"    columns added per widening (default 128)
  *        "psd_guard"        1 (default): after compression estimate lambda_min(K~) and, if negative,
  *                           add delta = 1.1*|lambda_min| to the diagonal so that the approximate
  *                           problem (eq. 8) stays convex, as Algorithm 3 presupposes; 0: off
@@ -97,7 +107,8 @@ int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int3
  * coordinate of largest variance), random sampling S = K Omega, interpolative decompositions level by
  * level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,
  * 1 <= r <= 96, h > 0, 0 < tol < 1.  Pivots of each decomposition are kept while
- * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 (EUNSUPPORTED beyond).
+ * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 and s <= 2048 (s <= 1024 for
+ * tol < 3e-5), EUNSUPPORTED beyond.
  * Drops any previous compression and factorization held by the context.
  * hss_compress draws Omega itself (Philox4x32-10 + Box-Muller, option "seed");
  * hss_compress_with_samples takes Omega (dev, n x s row-major, rows in the order of F) from the caller. */
@@ -172,6 +183,8 @@ typedef struct hss_stats_t {
     double  t_sample_kernel;           /* seconds of the K*Omega kernel alone (HIP events on the stream)      */
     int32_t warnings;                  /* OR of HSS_W* seen since the last compress                         */
     int32_t reserved;
+    int64_t sample_width_used;         /* columns of the sample the decompositions ended up using (adaptive width) */
+    int64_t nodes_redone;              /* node decompositions repeated after the sample was widened              */
 } hss_stats_t;
 int hss_stats(hss_ctx* ctx, hss_stats_t* out_host);
 

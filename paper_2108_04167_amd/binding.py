@@ -23,7 +23,8 @@ class HssStats(C.Structure):
                 ("sample_flops", C.c_double), ("delta", C.c_double), ("beta", C.c_double),
                 ("t_tree", C.c_double), ("t_sample", C.c_double), ("t_levels", C.c_double),
                 ("t_guard", C.c_double), ("t_factor", C.c_double), ("t_sample_kernel", C.c_double),
-                ("warnings", C.c_int32), ("reserved", C.c_int32)]
+                ("warnings", C.c_int32), ("reserved", C.c_int32),
+                ("sample_width_used", C.c_int64), ("nodes_redone", C.c_int64)]
 
 
 # name -> (restype, argtypes): every symbol include/hss_svm.h declares

@@ -46,6 +46,8 @@ int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
     else if (!strcmp(key, "max_rank")) { if (v < 0) return HSS_EINVAL; c->opt_max_rank = v; }
     else if (!strcmp(key, "seed")) c->opt_seed = v;
     else if (!strcmp(key, "psd_guard")) c->opt_guard = v ? 1 : 0;
+    else if (!strcmp(key, "adaptive_start")) { if (v < 0) return HSS_EINVAL; c->opt_adapt_start = v; }
+    else if (!strcmp(key, "adaptive_step")) { if (v < 1) return HSS_EINVAL; c->opt_adapt_step = v; }
     else return HSS_EINVAL;
     return HSS_OK;
 }
@@ -290,6 +292,7 @@ int hss_stats(hss_ctx* c, hss_stats_t* o) {
     memset(o, 0, sizeof(*o));
     o->n = c->n; o->r = c->r; o->leaf = c->leaf; o->levels = c->L;
     o->sample_width = c->s; o->rank_cap = c->kcap;
+    o->sample_width_used = c->width_used; o->nodes_redone = c->nodes_redone;
     if (c->compressed) {
         for (int l = 1; l <= c->L; ++l)
             for (int t = 0; t < c->lev[l].N; ++t) {

@@ -124,6 +124,10 @@ int sample_launch(hipStream_t st, const double* Fp, const double* nu, const doub
                   int64_t n_pad, int r_pad, int s_pad, double h);
 int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
                        const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int s_pad, double h);
+// The same for a window of `width` columns (a multiple of 128) of arrays with leading dimension ld.
+int sample_launch_window(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                         const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
+                         double h);
 int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad);
 // Fp[i, :] = F[perm[i], :] zero padded to r_pad columns; rows >= n are zeroed.  perm == nullptr: identity.
 int gather_pad_rows_launch(hipStream_t st, const double* F, const int64_t* perm, double* Fp, int64_t n, int64_t n_pad,

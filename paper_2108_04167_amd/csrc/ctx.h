@@ -21,6 +21,7 @@ struct Level {
     DevBuf U;                               // (msz x rk) row-major per node, at uoff
     DevBuf J;                               // int32 skeleton rows (local), at koff
     DevBuf skel;                            // int64 skeleton points (cluster-tree order), at koff
+    DevBuf rowmap;                          // int64 row of the level's sample block behind each skeleton, at koff
     DevBuf B;                               // (k_a x k_b) per inner node, at boff
     // ULV factors
     std::vector<char> pass;                 // 1: rank == size, nothing eliminated at this node
@@ -53,6 +54,7 @@ struct hss_ctx {
     hipStream_t stream = nullptr;
     // options
     int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
+    int64_t opt_adapt_start = 0, opt_adapt_step = 128;   // adaptive sample width: first width (0 = off), increment
     double  opt_abs_tol = 1e-8;
     // problem
     bool compressed = false, factored = false;
@@ -60,6 +62,8 @@ struct hss_ctx {
     int r = 0, r_pad = 0, leaf = 0, L = 0, s = 0, s_pad = 0, kcap = 0;
     double h = 0.0, tol = 0.0, delta = 0.0, beta = -1.0;
     int warnings = 0;
+    int width_used = 0;                     // sample columns the decompositions ended up using
+    int64_t nodes_redone = 0;               // node decompositions repeated after widening the sample
     DevBuf Fp, nu, yp, perm, Dleaf;
     std::vector<int64_t> perm_host;
     std::vector<Level> lev;                 // 0 .. L

@@ -245,12 +245,25 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     const int s = Omega ? s_in : (int)c->opt_s;
     if (s < 1) return HSS_EINVAL;
     const int s_pad = (int)round_up(s, 128);
-    if (s_pad > 512) return HSS_EUNSUPPORTED;
-    const int64_t p_over = c->opt_p >= 0 ? c->opt_p : (int64_t)s / 2;
-    int64_t kcap = c->opt_max_rank > 0 ? c->opt_max_rank : (int64_t)s - p_over;
+    if (s_pad > 2048) return HSS_EUNSUPPORTED;
+    // The Gram form of the interpolative decomposition resolves pivots down to about 1e-7 of the largest one;
+    // it is used when the relative stop threshold stays well above that, the Gram-Schmidt form (rows of at most
+    // 1024 columns) otherwise.
+    const bool gram_id = tol / 10.0 >= 3e-6;
+    if (!gram_id && s_pad > 1024) return HSS_EUNSUPPORTED;
+    // Adaptive sample width (option "adaptive_start" > 0): the decompositions first see `width` columns; the rank
+    // cap at width w is w - p(w), never above the final cap.
+    const bool adaptive = c->opt_adapt_start > 0 && c->opt_adapt_start < s;
+    const int step = (int)c->opt_adapt_step;
+    if (adaptive && (s % 128 || c->opt_adapt_start % 128 || step < 128 || step % 128)) return HSS_EINVAL;
+    auto cap_at = [&](int64_t w) { return w - (c->opt_p >= 0 ? c->opt_p : w / 2); };
+    int64_t kcap = c->opt_max_rank > 0 ? c->opt_max_rank : cap_at(s);
     if (kcap > s) kcap = s;
+    if (adaptive && kcap > cap_at(s)) kcap = cap_at(s);      // the final cap is the full sample's at most
     if (kcap < 1) return HSS_EINVAL;
     if (kcap > 512) return HSS_EUNSUPPORTED;
+    int width = adaptive ? (int)c->opt_adapt_start : s;
+    if (adaptive && cap_at(width) < 1) return HSS_EINVAL;
     int L = 0;
     while ((int64_t(1) << L) < nl) ++L;
 
@@ -260,6 +273,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
     c->h = h; c->tol = tol; c->delta = 0.0; c->beta = -1.0; c->warnings = 0;
+    c->width_used = width; c->nodes_redone = 0;
     c->r_pad = feature_pad(r);
     c->n_pad = round_up(n, 256);
     const int r_pad = c->r_pad;
@@ -295,35 +309,64 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     HIP_TRY(hipStreamSynchronize(st));
     c->t_tree = wall() - t0;
 
-    // ---- sampling ----
-    DevBuf S0, S1, Om0, Om1, Wk;
+    // ---- Omega (all s columns) and the first `width` columns of S = K Omega ----
+    // Two pairs of n_pad x s_pad buffers: level l works in pair (L - l) & 1.  A column of the rows handed from
+    // level to level depends on the same column of S and Omega only, so a column window [c0, c1) that is sampled
+    // later travels up through the finished levels on its own, in the same buffers (the wider columns of the
+    // pairs are not touched before that; those of pair 0 hold Omega as drawn).
+    DevBuf Sb[2], Ob[2], Wk;
     const size_t nsbytes = sizeof(double) * (size_t)n_pad * s_pad;
-    HSS_TRY(S0.reserve(nsbytes));
-    HSS_TRY(Om0.reserve(nsbytes));
+    const int LD = s_pad;
+    HSS_TRY(Sb[0].reserve(nsbytes));
+    HSS_TRY(Ob[0].reserve(nsbytes));
     t0 = wall();
-    if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Om0.as<double>(), n, n_pad, s, s_pad));
-    else HSS_TRY(omega_fill_launch(st, Om0.as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
-    hipEvent_t ev0, ev1;
-    HIP_TRY(hipEventCreate(&ev0));
-    HIP_TRY(hipEventCreate(&ev1));
-    HIP_TRY(hipEventRecord(ev0, st));
-    int src = sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Om0.as<double>(), S0.as<double>(), n_pad, r_pad,
-                            s_pad, h);
-    (void)hipEventRecord(ev1, st);
-    hipError_t serr = hipStreamSynchronize(st);
-    float ms = 0.f;
-    if (src >= 0 && serr == hipSuccess) (void)hipEventElapsedTime(&ms, ev0, ev1);
-    (void)hipEventDestroy(ev0);
-    (void)hipEventDestroy(ev1);
-    if (src < 0) return src;
-    if (serr != hipSuccess) return HSS_EHIP;
-    c->t_sample_kernel = ms * 1e-3;
+    if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Ob[0].as<double>(), n, n_pad, s, s_pad));
+    else HSS_TRY(omega_fill_launch(st, Ob[0].as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
+    c->t_sample_kernel = 0.0;
+    c->sample_flops = 0.0;
+    struct EventPair {      // destroyed on every way out of the function
+        hipEvent_t a = nullptr, b = nullptr;
+        ~EventPair() {
+            if (a) (void)hipEventDestroy(a);
+            if (b) (void)hipEventDestroy(b);
+        }
+    } evp;
+    HIP_TRY(hipEventCreate(&evp.a));
+    HIP_TRY(hipEventCreate(&evp.b));
+    const hipEvent_t ev0 = evp.a, ev1 = evp.b;
+    // S[:, c0:c1) = K Omega[:, c0:c1) into pair 0 (the leaf level's), timed with events on the stream
+    auto sample_columns = [&](int c0, int c1) -> int {
+        const int w = (int)round_up(c1 - c0, 128);
+        if (hipEventRecord(ev0, st) != hipSuccess) return HSS_EHIP;
+        int src = sample_launch_window(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(),
+                                       c->nu.as<double>(), n_pad, Ob[0].as<double>() + c0, Sb[0].as<double>() + c0, r_pad, w,
+                                       LD, h);
+        (void)hipEventRecord(ev1, st);
+        hipError_t serr = hipStreamSynchronize(st);
+        float ms = 0.f;
+        if (src >= 0 && serr == hipSuccess) (void)hipEventElapsedTime(&ms, ev0, ev1);
+        if (src < 0) return src;
+        if (serr != hipSuccess) return HSS_EHIP;
+        c->t_sample_kernel += ms * 1e-3;
+        c->sample_flops += 2.0 * (double)n * (double)n * (double)((c1 - c0) + r);
+        return HSS_OK;
+    };
+    HSS_TRY(sample_columns(0, width));
     c->t_sample = wall() - t0;
-    c->sample_flops = 2.0 * (double)n * (double)n * (double)(s + r);
 
     // ---- leaf level: D_t and S_t = S - D Omega ----
     t0 = wall();
     HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)n * leaf));
+    // columns [c0, c1) of the leaf sample rows:  S_t -= D_t Omega_t
+    auto leaf_columns = [&](int c0, int c1) -> int {
+        Level& lv = c->lev[L];
+        std::vector<GemmItem> gm(lv.N);
+        const int w = (int)round_up(c1 - c0, 128);
+        for (int t = 0; t < lv.N; ++t)
+            gm[t] = GemmItem{c->Dleaf.as<double>() + (size_t)t * leaf * leaf, Ob[0].as<double>() + (size_t)t * leaf * LD + c0,
+                             Sb[0].as<double>() + (size_t)t * leaf * LD + c0, leaf, w, leaf, leaf, LD, LD};
+        return bgemm_host(st, c->arena, gm, false, false, -1.0, 1.0);
+    };
     {
         Level& lv = c->lev[L];
         lv.N = (int)nl;
@@ -332,26 +375,19 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         for (int t = 0; t <= lv.N; ++t) lv.moff[t] = (int64_t)t * leaf;
         lv.maxm = leaf;
         std::vector<KBItem> kb(lv.N);
-        std::vector<GemmItem> gm(lv.N);
-        for (int t = 0; t < lv.N; ++t) {
-            double* D = c->Dleaf.as<double>() + (size_t)t * leaf * leaf;
-            kb[t] = KBItem{nullptr, nullptr, (int64_t)t * leaf, (int64_t)t * leaf, D, leaf, leaf, leaf, 0};
-            gm[t] = GemmItem{D, Om0.as<double>() + (size_t)t * leaf * s_pad, S0.as<double>() + (size_t)t * leaf * s_pad,
-                             leaf, s_pad, leaf, leaf, s_pad, s_pad};
-        }
+        for (int t = 0; t < lv.N; ++t)
+            kb[t] = KBItem{nullptr, nullptr, (int64_t)t * leaf, (int64_t)t * leaf,
+                           c->Dleaf.as<double>() + (size_t)t * leaf * leaf, leaf, leaf, leaf, 0};
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
-        if (L >= 1) HSS_TRY(bgemm_host(st, c->arena, gm, false, false, -1.0, 1.0));
+        if (L >= 1) HSS_TRY(leaf_columns(0, width));
     }
-    // The Gram form of the interpolative decomposition resolves pivots down to about 1e-7 of the largest one;
-    // it is used when the relative stop threshold stays well above that, the Gram-Schmidt form otherwise.
-    const bool gram_id = tol / 10.0 >= 3e-6;
     if (L >= 1) {
-        HSS_TRY(S1.reserve(nsbytes));
-        HSS_TRY(Om1.reserve(nsbytes));
+        HSS_TRY(Sb[1].reserve(nsbytes));
+        HSS_TRY(Ob[1].reserve(nsbytes));
         if (!gram_id) HSS_TRY(Wk.reserve(nsbytes));
     }
     const int kc = (int)kcap;
-    DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, rowmap, Gm, d_goff;
+    DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, Gm, d_goff, d_active;
     if (L >= 1) {
         HSS_TRY(Lc.reserve(sizeof(double) * (size_t)n * kc));
         HSS_TRY(norms0.reserve(sizeof(double) * n));
@@ -361,58 +397,128 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         HSS_TRY(rkd.reserve(sizeof(int) * nl));
         HSS_TRY(done.reserve(sizeof(int) * nl));
         HSS_TRY(r11.reserve(sizeof(double) * nl));
-        HSS_TRY(rowmap.reserve(sizeof(int64_t) * n));
+        HSS_TRY(d_active.reserve(sizeof(int) * nl));
     }
-    double* Acur = S0.as<double>();
-    double* Anext = S1.as<double>();
-    double* Ocur = Om0.as<double>();
-    double* Onext = Om1.as<double>();
-    int64_t rank_sum = 0;
-    for (int l = L; l >= 1; --l) {
+    // Columns [c0, c1) of the rows level l hands to its parent level (l >= 2), from the level's finished
+    // decompositions:  S~ = S_t(J,:),  Om~ = U^T Om_t  laid out as the parent's rows, then
+    // [S~_a - B Om~_b; S~_b - B^T Om~_a].
+    auto push_columns = [&](int l, int c0, int c1) -> int {
+        Level& lv = c->lev[l];
+        Level& pl = c->lev[l - 1];
+        const int N = lv.N;
+        const int w = (int)round_up(c1 - c0, 128);
+        const int pc = (L - l) & 1, pn = pc ^ 1;
+        const double* Acur = Sb[pc].as<double>() + c0;
+        const double* Ocur = Ob[pc].as<double>() + c0;
+        double* Anext = Sb[pn].as<double>() + c0;
+        double* Onext = Ob[pn].as<double>() + c0;
+        const int64_t ktot = lv.koff[N];
+        HSS_TRY(copy_rows_launch(st, Anext, LD, Acur, LD, lv.rowmap.as<int64_t>(), ktot, w));
+        std::vector<GemmItem> g1(N);
+        for (int t = 0; t < N; ++t)
+            g1[t] = GemmItem{lv.U.as<double>() + lv.uoff[t], Ocur + (size_t)lv.moff[t] * LD, Onext + (size_t)lv.koff[t] * LD,
+                             lv.rk[t], w, lv.msz[t], lv.rk[t], LD, LD};
+        HSS_TRY(bgemm_host(st, c->arena, g1, true, false, 1.0, 0.0));
+        std::vector<GemmItem> g2(pl.N), g3(pl.N);
+        for (int i = 0; i < pl.N; ++i) {
+            const int a = 2 * i, b = 2 * i + 1;
+            const double* B = pl.B.as<double>() + pl.boff[i];
+            g2[i] = GemmItem{B, Onext + (size_t)lv.koff[b] * LD, Anext + (size_t)lv.koff[a] * LD, lv.rk[a], w, lv.rk[b],
+                             lv.rk[b], LD, LD};
+            g3[i] = GemmItem{B, Onext + (size_t)lv.koff[a] * LD, Anext + (size_t)lv.koff[b] * LD, lv.rk[b], w, lv.rk[a],
+                             lv.rk[b], LD, LD};
+        }
+        HSS_TRY(bgemm_host(st, c->arena, g2, false, false, -1.0, 1.0));
+        HSS_TRY(bgemm_host(st, c->arena, g3, true, false, -1.0, 1.0));
+        return HSS_OK;
+    };
+    int status = HSS_OK;
+    for (int l = L; l >= 1 && status >= 0; --l) {
         Level& lv = c->lev[l];
         const int N = lv.N;
         const int64_t rows = lv.moff[N];
+        const int pc = (L - l) & 1;
+        double* Acur = Sb[pc].as<double>();
         HSS_TRY(upload(c, lv.d_moff, lv.moff));
-        // interpolative decompositions of all nodes of the level
+        // interpolative decompositions of the nodes of the level; with the adaptive width, again for the nodes
+        // that the sample's rank cap cut, after widening the sample
         IdLevelArgs ia;
-        ia.W = Wk.as<double>(); ia.ld = s_pad; ia.moff = lv.d_moff.as<int64_t>(); ia.kcap = (int)kcap; ia.kc = kc;
+        ia.W = Wk.as<double>(); ia.moff = lv.d_moff.as<int64_t>(); ia.kc = kc;
         ia.rows_per_block = 32; ia.rel = tol / 10.0; ia.abs_tol = c->opt_abs_tol;
         ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>(); ia.rk = rkd.as<int>();
         ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>();
+        ia.active = nullptr;
+        std::vector<int> active(N, 1);
+        std::vector<int64_t> goff;
         if (gram_id) {
-            // pivoted Cholesky of the nodes' Gram matrices S_t S_t^T (one workgroup per node, all steps in one launch)
-            std::vector<int64_t> goff(N + 1, 0);
+            goff.assign(N + 1, 0);
             for (int t = 0; t < N; ++t) goff[t + 1] = goff[t] + (int64_t)lv.msz[t] * lv.msz[t];
             HSS_TRY(Gm.reserve(sizeof(double) * goff[N]));
             HSS_TRY(upload(c, d_goff, goff));
-            std::vector<GemmItem> gg(N);
-            for (int t = 0; t < N; ++t) {
-                const double* St = Acur + (size_t)lv.moff[t] * s_pad;
-                gg[t] = GemmItem{St, St, Gm.as<double>() + goff[t], lv.msz[t], lv.msz[t], s_pad, s_pad, s_pad, lv.msz[t]};
-            }
-            HSS_TRY(bgemm_host(st, c->arena, gg, false, true, 1.0, 0.0));
-            HSS_TRY(id_chol(st, ia, N, lv.maxm, Gm.as<double>(), d_goff.as<int64_t>()));
-        } else {
-            // row-pivoted Gram-Schmidt on a work copy of the sample rows, one launch per pivot step
-            HIP_TRY(hipMemcpyAsync(Wk.p, Acur, sizeof(double) * (size_t)rows * s_pad, hipMemcpyDeviceToDevice, st));
-            HSS_TRY(id_init(st, ia, rows, N, norms0.as<double>()));
-            HSS_TRY(id_steps(st, ia, N, lv.maxm, norms0.as<double>(), norms1.as<double>()));
         }
-        lv.rk.resize(N);
-        HIP_TRY(hipMemcpyAsync(lv.rk.data(), rkd.p, sizeof(int) * N, hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipStreamSynchronize(st));
-        c->arena.reset();
+        lv.rk.assign(N, 0);
+        for (bool first = true;; first = false) {
+            const int cap = (int)std::min<int64_t>(adaptive ? cap_at(width) : kcap, kcap);
+            ia.kcap = cap;
+            const int wpad = (int)round_up(width, 128);      // columns width .. wpad are zero
+            ia.ld = gram_id ? LD : wpad;
+            if (!first) {
+                HSS_TRY(upload(c, d_active, active));
+                ia.active = d_active.as<int>();
+            }
+            if (gram_id) {
+                // pivoted Cholesky of the nodes' Gram matrices S_t S_t^T over the first `width` columns (one
+                // workgroup per node, all steps in one launch)
+                std::vector<GemmItem> gg;
+                for (int t = 0; t < N; ++t) {
+                    if (!active[t]) continue;
+                    const double* St = Acur + (size_t)lv.moff[t] * LD;
+                    gg.push_back(GemmItem{St, St, Gm.as<double>() + goff[t], lv.msz[t], lv.msz[t], wpad, LD, LD, lv.msz[t]});
+                }
+                HSS_TRY(bgemm_host(st, c->arena, gg, false, true, 1.0, 0.0));
+                HSS_TRY(id_chol(st, ia, N, lv.maxm, Gm.as<double>(), d_goff.as<int64_t>()));
+            } else {
+                // row-pivoted Gram-Schmidt on a tight work copy of the first `width` columns, one launch per step
+                HIP_TRY(hipMemcpy2DAsync(Wk.p, sizeof(double) * wpad, Acur, sizeof(double) * LD, sizeof(double) * wpad,
+                                         (size_t)rows, hipMemcpyDeviceToDevice, st));
+                HSS_TRY(id_init(st, ia, N, lv.maxm, norms0.as<double>()));
+                HSS_TRY(id_steps(st, ia, N, lv.maxm, norms0.as<double>(), norms1.as<double>()));
+            }
+            HIP_TRY(hipMemcpyAsync(lv.rk.data(), rkd.p, sizeof(int) * N, hipMemcpyDeviceToHost, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            c->arena.reset();
+            int ncut = 0;
+            for (int t = 0; t < N; ++t) {
+                const int k = lv.rk[t];
+                if (k < 1 || k > lv.msz[t]) return HSS_EHIP;   // the kernels guarantee 1 <= k <= size
+                active[t] = active[t] && k == cap && k < lv.msz[t];
+                ncut += active[t];
+            }
+            if (!adaptive || ncut == 0 || width >= s || cap >= kcap) break;
+            // widen: sample the next columns, take them through the leaf level and the finished levels
+            const int c0 = width, c1 = std::min(s, width + step);
+            const double tw = wall();
+            status = sample_columns(c0, c1);
+            if (status < 0) break;
+            const double tw1 = wall();
+            c->t_sample += tw1 - tw;
+            t0 += tw1 - tw;                                   // sampling time is not level time
+            status = leaf_columns(c0, c1);
+            for (int ll = L; ll > l && status >= 0; --ll) status = push_columns(ll, c0, c1);
+            if (status < 0) break;
+            width = c1;
+            c->nodes_redone += ncut;
+        }
+        if (status < 0) break;
         lv.koff.assign(N + 1, 0);
         lv.uoff.assign(N + 1, 0);
         lv.maxk = 0;
         for (int t = 0; t < N; ++t) {
             const int k = lv.rk[t];
-            if (k < 1 || k > lv.msz[t]) return HSS_EHIP;   // the kernels guarantee 1 <= k <= size
             lv.koff[t + 1] = lv.koff[t] + k;
             lv.uoff[t + 1] = lv.uoff[t] + (int64_t)k * lv.msz[t];
             lv.maxk = std::max(lv.maxk, k);
-            if (k == kcap && k < lv.msz[t]) c->warnings |= HSS_WRANK;
-            rank_sum += k;
+            if (active[t]) c->warnings |= HSS_WRANK;          // still cut by a cap
         }
         const int64_t ktot = lv.koff[N];
         HSS_TRY(upload(c, lv.d_koff, lv.koff));
@@ -420,12 +526,14 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         HSS_TRY(lv.U.reserve(sizeof(double) * lv.uoff[N]));
         HSS_TRY(lv.J.reserve(sizeof(int) * ktot));
         HSS_TRY(lv.skel.reserve(sizeof(int64_t) * ktot));
+        HSS_TRY(lv.rowmap.reserve(sizeof(int64_t) * ktot));
+        ia.active = nullptr;
         HSS_TRY(id_finish(st, ia, N, lv.maxm, lv.d_koff.as<int64_t>(), lv.d_uoff.as<int64_t>(), lv.U.as<double>(),
                           lv.J.as<int>()));
         HSS_TRY(rowmap_launch(st, lv.d_moff.as<int64_t>(), lv.d_koff.as<int64_t>(), jtmp.as<int>(), kc, N,
-                              rowmap.as<int64_t>()));
+                              lv.rowmap.as<int64_t>()));
         HSS_TRY(gather_index_launch(st, lv.skel.as<int64_t>(), l == L ? nullptr : c->lev[l + 1].skel.as<int64_t>(),
-                                    rowmap.as<int64_t>(), ktot));
+                                    lv.rowmap.as<int64_t>(), ktot));
         // parent level
         Level& pl = c->lev[l - 1];
         pl.N = N / 2;
@@ -447,30 +555,10 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
                            pl.B.as<double>() + pl.boff[i], lv.rk[a], lv.rk[b], lv.rk[b], 0};
         }
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
-        if (l - 1 >= 1) {
-            // S~ = S_t(J,:) and Om~ = U^T Om_t, laid out as the parent's rows
-            HSS_TRY(copy_rows_launch(st, Anext, s_pad, Acur, s_pad, rowmap.as<int64_t>(), ktot, s_pad));
-            std::vector<GemmItem> g1(N);
-            for (int t = 0; t < N; ++t)
-                g1[t] = GemmItem{lv.U.as<double>() + lv.uoff[t], Ocur + (size_t)lv.moff[t] * s_pad,
-                                 Onext + (size_t)lv.koff[t] * s_pad, lv.rk[t], s_pad, lv.msz[t], lv.rk[t], s_pad, s_pad};
-            HSS_TRY(bgemm_host(st, c->arena, g1, true, false, 1.0, 0.0));
-            // parent sample rows: [S~_a - B Om~_b; S~_b - B^T Om~_a]
-            std::vector<GemmItem> g2(pl.N), g3(pl.N);
-            for (int i = 0; i < pl.N; ++i) {
-                const int a = 2 * i, b = 2 * i + 1;
-                const double* B = pl.B.as<double>() + pl.boff[i];
-                g2[i] = GemmItem{B, Onext + (size_t)lv.koff[b] * s_pad, Anext + (size_t)lv.koff[a] * s_pad,
-                                 lv.rk[a], s_pad, lv.rk[b], lv.rk[b], s_pad, s_pad};
-                g3[i] = GemmItem{B, Onext + (size_t)lv.koff[a] * s_pad, Anext + (size_t)lv.koff[b] * s_pad,
-                                 lv.rk[b], s_pad, lv.rk[a], lv.rk[b], s_pad, s_pad};
-            }
-            HSS_TRY(bgemm_host(st, c->arena, g2, false, false, -1.0, 1.0));
-            HSS_TRY(bgemm_host(st, c->arena, g3, true, false, -1.0, 1.0));
-            std::swap(Acur, Anext);
-            std::swap(Ocur, Onext);
-        }
+        if (l - 1 >= 1) HSS_TRY(push_columns(l, 0, width));
     }
+    if (status < 0) return status;
+    c->width_used = width;
     // root bookkeeping
     {
         Level& rl = c->lev[0];
@@ -495,7 +583,6 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         if (l >= 1) c->generator_bytes += (int64_t)sizeof(double) * lv.uoff[lv.N];
         if (l < L) c->generator_bytes += (int64_t)sizeof(double) * lv.boff[lv.N];
     }
-    (void)rank_sum;
     HSS_TRY(build_matvec_tables(c));
     c->compressed = true;
     t0 = wall();

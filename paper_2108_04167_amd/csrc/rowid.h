@@ -16,9 +16,11 @@ struct IdLevelArgs {
     int*           rk;       // [nnodes] ranks (output)
     double*        Lc;       // [sum msz x kc] Gram-Schmidt coefficients
     int*           sel;      // [sum msz] 0 = not chosen, j+1 = chosen at step j
+    const int*     active;   // [nnodes] or null: nodes with active[t] == 0 are left exactly as an earlier run of
+                             // the same level left them (ranks, pivots, coefficients)
 };
 
-int id_init(hipStream_t st, const IdLevelArgs& a, int64_t nrows, int nnodes, double* norms0);
+int id_init(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* norms0);
 int id_steps(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* norms0, double* norms1);
 int id_finish(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, const int64_t* koff, const int64_t* uoff,
               double* U, int* J);

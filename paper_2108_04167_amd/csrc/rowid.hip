@@ -21,21 +21,34 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
-// norms0[i] = ||W_i||^2, sel[i] = 0.  One wavefront per row.
-__global__ __launch_bounds__(256) void id_init_kernel(const double* __restrict__ W, int ld, int64_t nrows,
-                                                      double* __restrict__ norms0, int* __restrict__ sel) {
-    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    int lane = threadIdx.x & 63;
-    if (row >= nrows) return;
-    double acc = 0.0;
-    for (int c = lane; c < ld; c += 64) {
-        double v = W[row * ld + c];
-        acc += v * v;
+// Start of a run for the nodes taking part in it: norms0[i] = ||W_i||^2, sel[i] = 0, rank 0, not done.
+// A node that sits the run out is marked done so that no step touches it.  One wavefront per row.
+__global__ __launch_bounds__(256) void id_init_kernel(IdLevelArgs a, double* __restrict__ norms0) {
+    const int node = blockIdx.x;
+    const int64_t m0 = a.moff[node];
+    const int msz = (int)(a.moff[node + 1] - m0);
+    const bool act = !a.active || a.active[node];
+    if (blockIdx.y == 0 && threadIdx.x == 0) {
+        a.done[node] = act ? 0 : 1;
+        if (act) a.rk[node] = 0;
     }
-    acc = wave_sum(acc);
-    if (lane == 0) {
-        norms0[row] = acc;
-        sel[row] = 0;
+    if (!act) return;
+    const int r0 = blockIdx.y * a.rows_per_block;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int rend = r0 + a.rows_per_block;
+    if (rend > msz) rend = msz;
+    for (int i = r0 + wave; i < rend; i += 4) {
+        const double* w = a.W + (size_t)(m0 + i) * a.ld;
+        double acc = 0.0;
+        for (int c = lane; c < a.ld; c += 64) {
+            double v = w[c];
+            acc += v * v;
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) {
+            norms0[m0 + i] = acc;
+            a.sel[m0 + i] = 0;
+        }
     }
 }
 
@@ -151,6 +164,7 @@ __global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __r
     extern __shared__ double sm[];
     constexpr int LDP = NB + 1;
     const int node = blockIdx.x;
+    if (a.active && !a.active[node]) return;
     const int64_t m0 = a.moff[node];
     const int msz = (int)(a.moff[node + 1] - m0);
     const int lim = msz < a.kcap ? msz : a.kcap;
@@ -356,13 +370,10 @@ __global__ __launch_bounds__(256) void id_finish_kernel(IdLevelArgs a, const int
 
 }  // namespace
 
-int id_init(hipStream_t st, const IdLevelArgs& a, int64_t nrows, int nnodes, double* norms0) {
-    if (nrows <= 0) return HSS_OK;
-    HIP_TRY(hipMemsetAsync(a.Lc, 0, sizeof(double) * (size_t)nrows * a.kc, st));
-    HIP_TRY(hipMemsetAsync(a.rk, 0, sizeof(int) * (size_t)nnodes, st));
-    HIP_TRY(hipMemsetAsync(a.done, 0, sizeof(int) * (size_t)nnodes, st));
-    hipLaunchKernelGGL(id_init_kernel, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, st, a.W, a.ld, nrows, norms0,
-                       a.sel);
+int id_init(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, double* norms0) {
+    if (nnodes <= 0 || maxmsz <= 0) return HSS_OK;
+    const unsigned yc = (unsigned)((maxmsz + a.rows_per_block - 1) / a.rows_per_block);
+    hipLaunchKernelGGL(id_init_kernel, dim3((unsigned)nnodes, yc), dim3(256), 0, st, a, norms0);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
@@ -379,6 +390,10 @@ int id_steps(hipStream_t st, const IdLevelArgs& a, int nnodes, int maxmsz, doubl
             case 4: hipLaunchKernelGGL(id_step_kernel<4>, grid, dim3(256), 0, st, a, j, nin, nout); break;
             case 6: hipLaunchKernelGGL(id_step_kernel<6>, grid, dim3(256), 0, st, a, j, nin, nout); break;
             case 8: hipLaunchKernelGGL(id_step_kernel<8>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 10: hipLaunchKernelGGL(id_step_kernel<10>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 12: hipLaunchKernelGGL(id_step_kernel<12>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 14: hipLaunchKernelGGL(id_step_kernel<14>, grid, dim3(256), 0, st, a, j, nin, nout); break;
+            case 16: hipLaunchKernelGGL(id_step_kernel<16>, grid, dim3(256), 0, st, a, j, nin, nout); break;
             default: return HSS_EUNSUPPORTED;
         }
     }

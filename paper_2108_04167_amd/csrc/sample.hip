@@ -58,6 +58,8 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
                                                       int n_pad, int s_pad, double inv2h2) {
     // rows of S: the points (Fr, nur), one workgroup per BMR of them; columns of K: the points (Fp, nu), n_pad of
     // them.  The two sets are the same for the compression sample and differ for the label assignment.
+    // s_pad is the leading dimension of Om and S; the grid's y extent fixes how many of their columns (from the
+    // pointers on) this launch computes, so a launch can fill a column window of wider arrays.
     static_assert(WR * WC == 8, "8 wavefronts");
     constexpr int BMR = 64 * WR;           // rows of S per workgroup
     constexpr int LDK = BMR + 1;           // leading dimension of the K tile (j-major); odd: the exp results of 16 lanes
@@ -253,12 +255,12 @@ size_t sample_smem(int r_pad) {
 
 template <int WR, int WC, int CT, int GP>
 int sample_go_g(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp, const double* nu,
-                const double* Om, double* S, int64_t n_pad, int s_pad, double inv2h2) {
+                const double* Om, double* S, int64_t n_pad, int width, int s_pad, double inv2h2) {
     size_t smem = sample_smem<WR>(28 * GP);
     auto kern = sample_kernel<WR, WC, CT, GP>;
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
-    dim3 grid((unsigned)(nr_pad / (64 * WR)), (unsigned)(s_pad / (16 * CT * WC)));
+    dim3 grid((unsigned)(nr_pad / (64 * WR)), (unsigned)(width / (16 * CT * WC)));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, Fr, nur, Fp, nu, Om, S, (int)n_pad, s_pad, inv2h2);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
@@ -266,12 +268,12 @@ int sample_go_g(hipStream_t st, const double* Fr, const double* nur, int64_t nr_
 
 template <int WR, int WC, int CT>
 int sample_go(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp, const double* nu,
-              const double* Om, double* S, int64_t n_pad, int r_pad, int s_pad, double inv2h2) {
+              const double* Om, double* S, int64_t n_pad, int r_pad, int width, int s_pad, double inv2h2) {
     switch (r_pad / 28) {
-        case 1: return sample_go_g<WR, WC, CT, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 2: return sample_go_g<WR, WC, CT, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 3: return sample_go_g<WR, WC, CT, 3>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
-        case 4: return sample_go_g<WR, WC, CT, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, s_pad, inv2h2);
+        case 1: return sample_go_g<WR, WC, CT, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, width, s_pad, inv2h2);
+        case 2: return sample_go_g<WR, WC, CT, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, width, s_pad, inv2h2);
+        case 3: return sample_go_g<WR, WC, CT, 3>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, width, s_pad, inv2h2);
+        case 4: return sample_go_g<WR, WC, CT, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, width, s_pad, inv2h2);
         default: return HSS_EUNSUPPORTED;
     }
 }
@@ -349,29 +351,39 @@ __global__ void omega_fill_kernel(double* __restrict__ Om, int64_t n, int64_t n_
 
 }  // namespace
 
-// S (nr_pad x s_pad) = K(rows, cols) Om with rows = the points (Fr, nur), cols = the points (Fp, nu); Om is
-// n_pad x s_pad.  Both point sets are padded (rows to a multiple of 256, features to r_pad).
-int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
-                       const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int s_pad, double h) {
-    if (n_pad % 256 || nr_pad % 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 || s_pad % 128 || s_pad < 128)
+// S (nr_pad x width) = K(rows, cols) Om with rows = the points (Fr, nur), cols = the points (Fp, nu); Om is
+// n_pad x width.  Both arrays have leading dimension ld >= width (a column window of wider arrays is a pointer
+// offset).  Both point sets are padded (rows to a multiple of 256, features to r_pad).
+int sample_launch_window(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                         const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
+                         double h) {
+    if (n_pad % 256 || nr_pad % 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 || width % 128 || width < 128 ||
+        ld < width || (ld & 1))
         return HSS_EUNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(Om) | reinterpret_cast<uintptr_t>(S)) & 15) return HSS_EUNSUPPORTED;
     const double inv2h2 = 1.0 / (2.0 * h * h);
-    // Widest block of S per workgroup whose column span divides s_pad and whose LDS footprint fits:
+    // Widest block of S per workgroup whose column span divides the width and whose LDS footprint fits:
     // 64 x 512, else 128 x 256 (64 x 256 when the feature tiles are too large), else 128 x 128 (64 x 128).
     const size_t lds_cap = 150 * 1024;
     const bool fit2 = sample_smem<2>(r_pad) <= lds_cap;
     if (sample_smem<1>(r_pad) > lds_cap) return HSS_EUNSUPPORTED;
-    if (s_pad % 512 == 0) return sample_go<1, 8, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
-    if (s_pad % 256 == 0)
-        return fit2 ? sample_go<2, 4, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
-                    : sample_go<1, 8, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
-    return fit2 ? sample_go<2, 4, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2)
-                : sample_go<1, 8, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, s_pad, inv2h2);
+    if (width % 512 == 0)
+        return sample_go<1, 8, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, width, ld, inv2h2);
+    if (width % 256 == 0)
+        return fit2 ? sample_go<2, 4, 4>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, width, ld, inv2h2)
+                    : sample_go<1, 8, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, width, ld, inv2h2);
+    return fit2 ? sample_go<2, 4, 2>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, width, ld, inv2h2)
+                : sample_go<1, 8, 1>(st, Fr, nur, nr_pad, Fp, nu, Om, S, n_pad, r_pad, width, ld, inv2h2);
+}
+
+int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                       const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int s_pad, double h) {
+    return sample_launch_window(st, Fr, nur, nr_pad, Fp, nu, n_pad, Om, S, r_pad, s_pad, s_pad, h);
 }
 
 int sample_launch(hipStream_t st, const double* Fp, const double* nu, const double* Om, double* S, int64_t n_pad,
                   int r_pad, int s_pad, double h) {
-    return sample_launch_rect(st, Fp, nu, n_pad, Fp, nu, n_pad, Om, S, r_pad, s_pad, h);
+    return sample_launch_window(st, Fp, nu, n_pad, Fp, nu, n_pad, Om, S, r_pad, s_pad, s_pad, h);
 }
 
 int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad) {

@@ -128,7 +128,7 @@ int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, co
     IdLevelArgs ia;
     ia.W = W.as<double>(); ia.ld = ld; ia.moff = moff.as<int64_t>(); ia.kcap = kcap; ia.kc = kcap; ia.rows_per_block = 32;
     ia.rel = rel; ia.abs_tol = abs_tol; ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>();
-    ia.rk = rk.as<int>(); ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>();
+    ia.rk = rk.as<int>(); ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>(); ia.active = nullptr;
     if (gram) {
         DescArena ar;
         HSS_TRY(ar.init(size_t(8) << 20));
@@ -152,7 +152,7 @@ int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, co
         HSS_TRY(id_chol(st, ia, nnodes, maxm, Gm.as<double>(), goffd.as<int64_t>()));
         HIP_TRY(hipStreamSynchronize(st));   // the arena and the Gram matrices go out of scope
     } else {
-        HSS_TRY(id_init(st, ia, rows, nnodes, n0.as<double>()));
+        HSS_TRY(id_init(st, ia, nnodes, maxm, n0.as<double>()));
         HSS_TRY(id_steps(st, ia, nnodes, maxm, n0.as<double>(), n1.as<double>()));
     }
     HIP_TRY(hipMemcpyAsync(ranks_host, rk.p, sizeof(int) * nnodes, hipMemcpyDeviceToHost, st));

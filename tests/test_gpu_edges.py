@@ -114,8 +114,45 @@ def test_limits_are_rejected_not_run():
     with pytest.raises(binding.HssError) as e:            # leaf above 1024
         ctx.hss_compress(_dev(w.F), y, 1.0, 2048, 1e-3)
     assert e.value.code == binding.HSS_EUNSUPPORTED
-    ctx.hss_set_i64("sample_width", 640)
+    ctx.hss_set_i64("sample_width", 2049)                 # sample wider than 2048 columns
     with pytest.raises(binding.HssError) as e:
         ctx.hss_compress(_dev(w.F), y, 1.0, 64, 1e-3)
     assert e.value.code == binding.HSS_EUNSUPPORTED
+    ctx.hss_set_i64("sample_width", 1152)                 # rank cap 576 > 512
+    with pytest.raises(binding.HssError) as e:
+        ctx.hss_compress(_dev(w.F), y, 1.0, 64, 1e-3)
+    assert e.value.code == binding.HSS_EUNSUPPORTED
+    ctx.hss_set_i64("max_rank", 512)                      # Gram-Schmidt form (tol < 3e-5): at most 1024 columns
+    with pytest.raises(binding.HssError) as e:
+        ctx.hss_compress(_dev(w.F), y, 1.0, 64, 1e-6)
+    assert e.value.code == binding.HSS_EUNSUPPORTED
+    ctx.close()
+
+
+def test_wide_sample_1024_columns_rank_cap_512():
+    """The widest default configuration: 1024 sample columns, rank cap 512 (nodes of 1024 rows)."""
+    from gpu_helpers import oracle_hss_from_export
+    w = synth.make_workload(3, n=4096, leaf=256, s=1024)
+    ctx = binding.Context()
+    rc = ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol, _dev(w.omega()))
+    st = ctx.hss_stats()
+    assert rc >= 0 and st["rank_cap"] == 512 and st["sample_width"] == 1024
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    H = oracle_hss_from_export(exp)
+    v = np.random.default_rng(0).standard_normal(w.n)
+    ctx.hss_ulv_factor(1.0)
+    x = _dev(v)
+    ctx.hss_ulv_solve(x)
+    Fz = oulv.ulv_factor(H, 1.0)
+    ref = np.empty(w.n)
+    ref[perm] = oulv.ulv_solve(Fz, v[perm])
+    assert np.linalg.norm(x.cpu().numpy() - ref) <= 1e-10 * np.linalg.norm(ref)
+    # as good as the oracle's compression of the same sample
+    Fp = w.F[perm]
+    K = gaussian_kernel(Fp, Fp, w.h)
+    err = np.linalg.norm(K - ohss.densify(oracle_hss_from_export(exp, with_shift=False))) / np.linalg.norm(K)
+    Ho = ohss.compress(Fp, w.h, w.leaf, w.omega()[perm], w.tol / 10.0, 1e-8, 512)
+    err_or = np.linalg.norm(K - ohss.densify(Ho)) / np.linalg.norm(K)
+    assert err <= max(w.tol, 1.5 * err_or), (err, err_or)
     ctx.close()
