@@ -106,6 +106,14 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="also run one plain device-to-device copy of this many bytes (reference for HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-width", type=int, default=0, help="override the workload's sample width s (largest width "
+                    "with --adaptive-start)")
+    ap.add_argument("--adaptive-start", type=int, default=0, help="adaptive sample width: first width (0 = off)")
+    ap.add_argument("--adaptive-step", type=int, default=128)
+    ap.add_argument("--oversample", type=int, default=-1, help="oversampling p (rank cap = width - p; default width/2)")
+    ap.add_argument("--max-rank", type=int, default=0)
+    ap.add_argument("--graph", action="store_true", help="replay the ADMM iterations from a HIP graph (A/B; default eager)")
+    ap.add_argument("--no-merge-top", action="store_true", help="one launch per tree level in the solve (A/B)")
     ap.add_argument("--sweep", action="store_true",
                     help="time the workload's C x beta grid instead (one compression, one factorization per beta, "
                          "the C values of a beta in lockstep); prints its own JSON line")
@@ -131,7 +139,20 @@ def main():
     F = torch.tensor(w.F, device=dev)
     y = torch.tensor(w.y, device=dev)
     ctx = binding.Context()
+    if args.sample_width:
+        w.s = args.sample_width
     ctx.hss_set_i64("sample_width", w.s)
+    if args.adaptive_start:
+        ctx.hss_set_i64("adaptive_start", args.adaptive_start)
+        ctx.hss_set_i64("adaptive_step", args.adaptive_step)
+    if args.oversample >= 0:
+        ctx.hss_set_i64("oversample", args.oversample)
+    if args.max_rank:
+        ctx.hss_set_i64("max_rank", args.max_rank)
+    if args.graph:
+        ctx.hss_set_i64("graph", 1)
+    if args.no_merge_top:
+        ctx.hss_set_i64("merge_top", 0)
     if args.sweep:
         sweep(args, w, ctx, F, y)
         return
@@ -165,7 +186,7 @@ def main():
     t_kernel /= args.steps
     t_solve_iter /= args.steps
     n, r, s = w.n, w.r, w.s
-    flops = 2.0 * n * n * (s + r)
+    flops = st["sample_flops"]        # 2 n^2 (columns + r) summed over the sampling launches of one compression
     tf = flops / t_kernel / 1e12
     solve_gbs = st2["factor_bytes"] / t_solve_iter / 1e9
 
@@ -196,7 +217,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg}" + (f" cut to n={n}" if args.n else ""), "n": n, "r": r, "h": w.h, "C": w.C, "leaf": w.leaf, "tol": w.tol,
-                   "sample_width": s, "rank_cap": st["rank_cap"], "beta": w.beta, "admm_iterations": w.maxit},
+                   "sample_width": s, "sample_width_used": st["sample_width_used"], "rank_cap": st["rank_cap"],
+                   "beta": w.beta, "admm_iterations": w.maxit},
         "phases_s": {"tree": st["t_tree"], "sampling": st["t_sample"], "levels": st["t_levels"], "guard": st["t_guard"],
                      "factor": st2["t_factor"], "admm_and_bias": t_train - st2["t_factor"]},
         "roofline": {"kernel": "sample_kernel (S = K*Omega, fused Gram+exp+contraction)", "bound": "mfma",
@@ -208,7 +230,7 @@ def main():
                            "bytes_per_solve": st2["factor_bytes"], "bytes_per_solve_compact": st2["factor_bytes_compact"],
                            "seconds_per_iteration": t_solve_iter, "seconds_per_solve_median_of_64": t_solve_median},
         "model": {"delta": st["delta"], "rank_max": st["rank_max"], "nodes_at_cap": st["nodes_at_cap"],
-                  "rel_error_estimate": rel_err,
+                  "rel_error_estimate": rel_err, "tolerance_met": bool(rel_err <= w.tol and st["nodes_at_cap"] == 0),
                   "bias": out["bias"], "n_margin": out["n_margin"], "test_accuracy_pct": acc, "warnings": st2["warnings"]},
     }
     if not args.no_cpu_baseline:

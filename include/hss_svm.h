@@ -67,6 +67,16 @@ void hss_destroy(hss_ctx* ctx);
  *                           level by level)                                    (oversampling, end of Sec. 3.2)
  *        "max_rank"         explicit rank cap per node (default 0 = s - p)
  *        "seed"             seed of the counter-based generator that draws Omega (default 0)
+        "merge_top"        1 (default): the ULV solve replaces the levels from the root down to a cut level by one
+                           product with the inverse of the reduced matrix at the cut (chosen at factorization
+                           time so that a solve takes the least modelled time; at most 4096 rows); 0: every
+                           level is a launch of its own.  Set before hss_ulv_factor.
+        "graph"            1: admm_svm_train records two iterations (all launches of two ULV solves and two vector
+                           updates) into a HIP graph and replays it, on a stream of the library's own that is
+                           ordered after / before the context's stream by events; 0 (default): every launch is
+                           issued eagerly on the context's stream.  The iterates are the same either way; the
+                           replay measured 3 - 35 % slower per iteration than eager launches on gfx950, the host
+                           never being the bottleneck of an iteration.
         "adaptive_start"   s0 > 0: adaptive sample width (oversampling / truncation of every block to the
                            tolerance, end of Sec. 3.2).  The decompositions of a tree level first see the leading
                            s0 columns of the sample; while a node of the level is cut by the sample's rank cap

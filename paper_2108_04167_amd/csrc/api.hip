@@ -36,6 +36,11 @@ int hss_create(hss_ctx** out, void* hip_stream) {
 void hss_destroy(hss_ctx* ctx) {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->gstream) {
+        (void)hipStreamSynchronize(ctx->gstream);
+        (void)hipStreamDestroy(ctx->gstream);
+    }
+    if (ctx->gevent) (void)hipEventDestroy(ctx->gevent);
     delete ctx;
 }
 
@@ -46,6 +51,8 @@ int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
     else if (!strcmp(key, "max_rank")) { if (v < 0) return HSS_EINVAL; c->opt_max_rank = v; }
     else if (!strcmp(key, "seed")) c->opt_seed = v;
     else if (!strcmp(key, "psd_guard")) c->opt_guard = v ? 1 : 0;
+    else if (!strcmp(key, "merge_top")) c->opt_merge_top = v ? 1 : 0;
+    else if (!strcmp(key, "graph")) c->opt_graph = v ? 1 : 0;
     else if (!strcmp(key, "adaptive_start")) { if (v < 0) return HSS_EINVAL; c->opt_adapt_start = v; }
     else if (!strcmp(key, "adaptive_step")) { if (v < 1) return HSS_EINVAL; c->opt_adapt_step = v; }
     else return HSS_EINVAL;
@@ -208,7 +215,41 @@ int admm_svm_train_multi(hss_ctx* c, const double* C_list, int32_t nC, double be
         double* pa = part + 4 * VEC_BLOCKS;
         double* pb = pa + MAX_NRHS * VEC_BLOCKS;
         HSS_TRY(admm_start(st, v, n, nr, pa));
-        for (int it = 0; it < maxit; ++it) {
+        int it = 0;
+        if (c->opt_graph && maxit >= 16) {
+            // Two iterations (the partial-sum buffers alternate) recorded once into a HIP graph and replayed: the
+            // host then issues one launch per pair of iterations instead of one per tree level and sweep.  The
+            // recording runs on a stream of the library's own (a caller's stream may be the null stream, which
+            // cannot be captured), ordered after and before the caller's stream by events.
+            if (!c->gstream) HIP_TRY(hipStreamCreateWithFlags(&c->gstream, hipStreamNonBlocking));
+            if (!c->gevent) HIP_TRY(hipEventCreateWithFlags(&c->gevent, hipEventDisableTiming));
+            HIP_TRY(hipEventRecord(c->gevent, st));
+            HIP_TRY(hipStreamWaitEvent(c->gstream, c->gevent, 0));
+            hipGraph_t graph = nullptr;
+            hipGraphExec_t exec = nullptr;
+            HIP_TRY(hipStreamBeginCapture(c->gstream, hipStreamCaptureModeRelaxed));
+            c->stream = c->gstream;
+            int rc = ulv_solve_inplace(c, nr);
+            if (rc >= 0) rc = admm_step(c->gstream, v, n, nr, box, beta, w1, pa, pb);
+            if (rc >= 0) rc = ulv_solve_inplace(c, nr);
+            if (rc >= 0) rc = admm_step(c->gstream, v, n, nr, box, beta, w1, pb, pa);
+            c->stream = st;
+            hipError_t e = hipStreamEndCapture(c->gstream, &graph);
+            if (rc >= 0 && e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            if (rc >= 0 && e == hipSuccess)
+                for (; it + 2 <= maxit && e == hipSuccess; it += 2) e = hipGraphLaunch(exec, c->gstream);
+            if (e == hipSuccess) e = hipEventRecord(c->gevent, c->gstream);
+            if (e == hipSuccess) e = hipStreamWaitEvent(st, c->gevent, 0);
+            // the executable graph is destroyed once its launches have drained
+            if (exec) {
+                (void)hipStreamSynchronize(c->gstream);
+                (void)hipGraphExecDestroy(exec);
+            }
+            if (graph) (void)hipGraphDestroy(graph);
+            if (rc < 0) return rc;
+            if (e != hipSuccess) return HSS_EHIP;
+        }
+        for (; it < maxit; ++it) {
             HSS_TRY(ulv_solve_inplace(c, nr));
             HSS_TRY(admm_step(st, v, n, nr, box, beta, w1, pa, pb));
             std::swap(pa, pb);

@@ -52,8 +52,12 @@ struct Level {
 
 struct hss_ctx {
     hipStream_t stream = nullptr;
+    hipStream_t gstream = nullptr;          // the library's own stream for graph capture and replay (default priority)
+    hipEvent_t gevent = nullptr;            // orders gstream after / before the caller's stream
     // options
     int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
+    int64_t opt_graph = 0;                  // replay the ADMM iterations from a HIP graph (measured slower: off)
+    int64_t opt_merge_top = 1;              // merge the top levels of the solve into one dense operator
     int64_t opt_adapt_start = 0, opt_adapt_step = 128;   // adaptive sample width: first width (0 = off), increment
     double  opt_abs_tol = 1e-8;
     // problem
@@ -72,6 +76,12 @@ struct hss_ctx {
                                             // with nrhs interleaved right-hand sides a vector at pool + o lives at
                                             // pool + o * nrhs
     int root_m = 0;
+    // Top of the tree merged into one dense operator: levels 0 .. top_l are replaced by x = topT b on the vectors
+    // of level top_l (topT = inverse of the reduced matrix there, top_m x top_m); top_l = 0 with topT unset means
+    // the plain root solve through rootinv.
+    int top_l = 0, top_m = 0;
+    DevBuf topT;
+    double *top_in = nullptr, *top_out = nullptr;   // single-column pool pointers of the operator's input / output
     DevBuf flags;                           // int[4] device flags (bit 0: tiny pivot)
     DescArena arena;
     // fixed vectors (cluster-tree order)

@@ -27,6 +27,9 @@ struct GemvItem {            // y = alpha * op x + beta * y
 // A work item stands for 4 * rows_per_wave rows; maxm = widest node of the table (<= 1024).
 int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* work_dev, int nwork, int rows_per_wave,
                        bool vec, int nrhs, double* pool, int maxm);
+// out = T in for the dense top-of-tree operator T (M x M row-major, M even, <= 4096); in / out hold nrhs
+// interleaved right-hand sides
+int top_gemv_launch(hipStream_t st, const double* T, int M, const double* in, double* out, int nrhs);
 // vec: every M, N, lda of the table is even and every pointer 16-byte aligned
 int bgemv_launch(hipStream_t st, const GemvItem* items_dev, int nitems, int maxM, int maxN, bool vec, double alpha,
                  double beta);

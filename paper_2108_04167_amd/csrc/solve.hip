@@ -173,6 +173,60 @@ __global__ __launch_bounds__(256) void solve_gemv_kernel(const SolveItem* __rest
     }
 }
 
+// y = T x for the dense operator that stands for the top of the tree (all levels from the root down to a cut
+// level merged into the inverse of the reduced matrix at the cut): T is M x M row-major, M even, M <= 512 NCH.
+// A workgroup computes R rows for NR interleaved right-hand sides; thread t multiplies columns 2t, 2t+1 (+512 per
+// chunk) of every row with its share of x held in registers, rows streamed front to back as in the level kernel.
+template <int R, int NR, int NCH>
+__global__ __launch_bounds__(256) void top_gemv_kernel(const double* __restrict__ T, int M, const double* __restrict__ in,
+                                                       double* __restrict__ out) {
+    __shared__ double red[4][R][NR];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.x * R;
+    double x0[NCH][NR], x1[NCH][NR];
+#pragma unroll
+    for (int k = 0; k < NCH; ++k) {
+        const int c = 2 * tid + 512 * k;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) x0[k][j] = x1[k][j] = 0.0;
+        if (c < M) {
+            const double* src = in + (size_t)c * NR;
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {      // 2 NR consecutive doubles, 16 bytes at a time
+                const double2 t = *reinterpret_cast<const double2*>(src + 2 * q);
+                if (2 * q < NR) x0[k][2 * q] = t.x; else x1[k][2 * q - NR] = t.x;
+                if (2 * q + 1 < NR) x0[k][2 * q + 1] = t.y; else x1[k][2 * q + 1 - NR] = t.y;
+            }
+        }
+    }
+    double s[R][NR];
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+        const double* rowp = T + (size_t)(row0 + rr < M ? row0 + rr : M - 1) * M;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) s[rr][j] = 0.0;
+#pragma unroll
+        for (int k = 0; k < NCH; ++k) {
+            const int c = 2 * tid + 512 * k;
+            const v2d a = __builtin_nontemporal_load(reinterpret_cast<const v2d*>(rowp + (c < M ? c : 0)));
+#pragma unroll
+            for (int j = 0; j < NR; ++j) s[rr][j] += a.x * x0[k][j] + a.y * x1[k][j];
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr)
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const double v = wave_sum(s[rr][j]);
+            if (lane == 0) red[wave][rr][j] = v;
+        }
+    __syncthreads();
+    if (tid < R * NR) {
+        const int rr = tid / NR, j = tid - rr * NR;
+        if (row0 + rr < M) out[(size_t)(row0 + rr) * NR + j] = ((red[0][rr][j] + red[1][rr][j]) + red[2][rr][j]) + red[3][rr][j];
+    }
+}
+
 // Batched y = alpha * A x + beta * y for the HSS mat-vec, A (M x N, N <= 1024) row-major: a wavefront computes
 // four consecutive rows with the input vector in registers, as in the solve kernel; transposed products use a
 // transposed copy of the generator, so every product streams rows.  Items whose generator is a permutation
@@ -271,6 +325,27 @@ int solve_level_launch(hipStream_t st, const SolveItem* items_dev, const int2* w
 #undef HSS_SOLVE_CASE
 #undef HSS_SOLVE_K
 #undef HSS_SOLVE_GO
+    HIP_TRY(hipGetLastError());
+    return HSS_OK;
+}
+
+int top_gemv_launch(hipStream_t st, const double* T, int M, const double* in, double* out, int nrhs) {
+    if (M < 2 || (M & 1) || M > 4096) return HSS_EUNSUPPORTED;
+    if (nrhs != 1 && nrhs != 2 && nrhs != 4) return HSS_EINVAL;
+    const int nch = M <= 1024 ? 2 : (M <= 2048 ? 4 : 8);
+#define HSS_TOP_K(R, NR, NCH)                                                                              \
+    hipLaunchKernelGGL((top_gemv_kernel<R, NR, NCH>), dim3((unsigned)((M + R - 1) / R)), dim3(256), 0, st, T, M, in, out)
+#define HSS_TOP_GO(R, NR)                        \
+    do {                                         \
+        if (nch == 2) HSS_TOP_K(R, NR, 2);       \
+        else if (nch == 4) HSS_TOP_K(R, NR, 4);  \
+        else HSS_TOP_K(R, NR, 8);                \
+    } while (0)
+    if (nrhs == 1) HSS_TOP_GO(4, 1);
+    else if (nrhs == 2) HSS_TOP_GO(4, 2);
+    else HSS_TOP_GO(2, 4);
+#undef HSS_TOP_GO
+#undef HSS_TOP_K
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }

@@ -128,6 +128,10 @@ int build_solve_tables(hss_ctx* c) {
             for (int r0 = 0; r0 < m; r0 += rb) work.push_back(make_int2(t, r0));
             for (int r0 = 0; r0 < m; r0 += 4 * WIDE_ROWS_PER_WAVE) work_wide.push_back(make_int2(t, r0));
         }
+        if (l == c->top_l) {
+            c->top_in = my_bvec;
+            c->top_out = my_xvec;
+        }
         lv.nwork = (int)work.size();
         lv.nwork_wide = (int)work_wide.size();
         HSS_TRY(upload(c, lv.work_wide, work_wide));
@@ -136,6 +140,104 @@ int build_solve_tables(hss_ctx* c) {
         HSS_TRY(upload(c, lv.work, work));
         HIP_TRY(hipStreamSynchronize(c->stream));
     }
+    return HSS_OK;
+}
+
+// The cut level of the merged top.  One solve launches a kernel per level and sweep, each a dependent step of a
+// few microseconds however little it reads; near the root the levels are small, so the levels 0 .. tl are better
+// served by ONE product with the inverse of the reduced matrix at level tl (M x M, M = rows of level tl) although
+// that matrix may hold more entries than the factors it replaces.  Model: a launch costs 3.5 us plus its bytes at
+// 6.5 TB/s; tl minimises the modelled time of a solve.  M must be even and at most 4096.
+int choose_top_level(hss_ctx* c) {
+    const int L = c->L;
+    const double t_launch = 3.5e-6, bw = 6.5e12;
+    bool leaves_pass = L >= 1;
+    for (int t = 0; leaves_pass && t < c->lev[L].N; ++t) leaves_pass = c->lev[L].pass[t] != 0;
+    std::vector<double> t_level(L + 1, 0.0);      // one sweep of level l (l >= 1)
+    for (int l = 1; l <= L; ++l) {
+        if (l == L && leaves_pass) continue;
+        t_level[l] = t_launch + 8.0 * (double)c->lev[l].foff[c->lev[l].N] / bw;
+    }
+    int best = 0;
+    double best_t = 1e300;
+    for (int tl = 0; tl <= L; ++tl) {
+        const int64_t M = c->lev[tl].moff[c->lev[tl].N];
+        if (tl > 0 && (M > 4096 || (M & 1))) continue;
+        double t = t_launch + 8.0 * (double)M * (double)M / bw;
+        for (int l = tl + 1; l <= L; ++l) t += 2.0 * t_level[l];
+        if (t < best_t) { best_t = t; best = tl; }
+    }
+    return best;
+}
+
+// topT = inverse of the reduced matrix at level tl: the sweeps of the levels tl .. 0 .. tl applied to the identity,
+// level by level as batched matrix products with the operators of the factorization.
+int build_top_operator(hss_ctx* c, int tl) {
+    hipStream_t st = c->stream;
+    c->top_l = tl;
+    c->top_m = (int)c->lev[tl].moff[c->lev[tl].N];
+    if (tl == 0) return HSS_OK;                    // the root inverse itself, applied as a level
+    const int M = c->top_m;
+    const size_t dsz = sizeof(double);
+    std::vector<DevBuf> Bm(tl + 1), Xm(tl + 1), Ce(tl + 1);
+    for (int l = 0; l <= tl; ++l) {
+        Level& lv = c->lev[l];
+        const int64_t rows = lv.moff[lv.N], ke = rows - lv.koff[lv.N];
+        HSS_TRY(Bm[l].reserve(dsz * rows * M));
+        if (l < tl) HSS_TRY(Xm[l].reserve(dsz * rows * M));
+        HSS_TRY(Ce[l].reserve(dsz * std::max<int64_t>(ke, 1) * M));
+    }
+    HSS_TRY(c->topT.reserve(dsz * (size_t)M * M));
+    c->arena.reset();
+    HSS_TRY(bcopy(st, c->arena, {cp(nullptr, Bm[tl].as<double>(), M, M, M, M, COPY_IDENTITY)}));
+    for (int l = tl; l >= 1; --l) {                // up-sweep: [b_r'; c_e] = Mup b per node
+        Level& lv = c->lev[l];
+        std::vector<GemmItem> g;
+        std::vector<CopyItem> ci;
+        for (int t = 0; t < lv.N; ++t) {
+            const int m = lv.msz[t], k = lv.rk[t];
+            const double* b = Bm[l].as<double>() + (size_t)lv.moff[t] * M;
+            double* up = Bm[l - 1].as<double>() + (size_t)lv.koff[t] * M;
+            if (lv.pass[t]) {
+                ci.push_back(cp(b, up, m, M, M, M, COPY_PLAIN));
+                continue;
+            }
+            const double* Mu = lv.Mup.as<double>() + lv.foff[t];
+            g.push_back(gi(Mu, b, up, k, M, m, m, M, M));
+            g.push_back(gi(Mu + (size_t)k * m, b, Ce[l].as<double>() + (size_t)(lv.moff[t] - lv.koff[t]) * M, m - k, M, m, m, M, M));
+        }
+        HSS_TRY(bcopy(st, c->arena, ci));
+        HSS_TRY(bgemm_host(st, c->arena, g, false, false, 1.0, 0.0));
+    }
+    {
+        const int m = c->root_m;
+        double* x0 = tl == 0 ? c->topT.as<double>() : Xm[0].as<double>();
+        HSS_TRY(bgemm_host(st, c->arena, {gi(c->rootinv.as<double>(), Bm[0].as<double>(), x0, m, M, m, m, M, M)}, false, false,
+                           1.0, 0.0));
+    }
+    for (int l = 1; l <= tl; ++l) {                // down-sweep: x = Mdown [x_r; c_e] per node
+        Level& lv = c->lev[l];
+        double* xout = l == tl ? c->topT.as<double>() : Xm[l].as<double>();
+        std::vector<GemmItem> g1, g2;
+        std::vector<CopyItem> ci;
+        for (int t = 0; t < lv.N; ++t) {
+            const int m = lv.msz[t], k = lv.rk[t];
+            const double* xr = Xm[l - 1].as<double>() + (size_t)lv.koff[t] * M;
+            double* x = xout + (size_t)lv.moff[t] * M;
+            if (lv.pass[t]) {
+                ci.push_back(cp(xr, x, m, M, M, M, COPY_PLAIN));
+                continue;
+            }
+            const double* Md = lv.Mdown.as<double>() + lv.foff[t];
+            g1.push_back(gi(Md, xr, x, m, M, k, m, M, M));
+            g2.push_back(gi(Md + k, Ce[l].as<double>() + (size_t)(lv.moff[t] - lv.koff[t]) * M, x, m, M, m - k, m, M, M));
+        }
+        HSS_TRY(bcopy(st, c->arena, ci));
+        HSS_TRY(bgemm_host(st, c->arena, g1, false, false, 1.0, 0.0));
+        HSS_TRY(bgemm_host(st, c->arena, g2, false, false, 1.0, 1.0));
+    }
+    HIP_TRY(hipStreamSynchronize(st));             // the temporaries go out of scope
+    c->arena.reset();
     return HSS_OK;
 }
 
@@ -194,7 +296,6 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
             lv.foff[t + 1] = lv.foff[t] + (lv.pass[t] ? 0 : (int64_t)m * m);
             lv.kkoff[t + 1] = lv.kkoff[t] + (int64_t)k * k;
             if (!lv.pass[t]) {
-                bytes_solve += 2 * (int64_t)sizeof(double) * m * m;
                 const int64_t e = m - k;
                 bytes_compact += 2 * (int64_t)sizeof(double) * ((int64_t)m * k + e * e + (int64_t)k * e);
             }
@@ -420,9 +521,12 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
         rl.foff = {0, 0};
         const int m = rl.msz[0];
         HSS_TRY(invert_root(c, Dbuf[cur].as<double>(), m, tiny));
-        bytes_solve += (int64_t)sizeof(double) * m * m;
         bytes_compact += (int64_t)sizeof(double) * m * m;
     }
+    // merged top: what a solve reads is the cut level's operator plus the operators of the levels below the cut
+    HSS_TRY(build_top_operator(c, c->opt_merge_top ? choose_top_level(c) : 0));
+    bytes_solve = (int64_t)sizeof(double) * c->top_m * c->top_m;
+    for (int l = c->top_l + 1; l <= L; ++l) bytes_solve += 2 * (int64_t)sizeof(double) * c->lev[l].foff[c->lev[l].N];
     HSS_TRY(build_solve_tables(c));
     int fl[4] = {0, 0, 0, 0};
     HIP_TRY(hipMemcpyAsync(fl, c->flags.p, sizeof(fl), hipMemcpyDeviceToHost, st));
@@ -450,13 +554,19 @@ int ulv_solve_inplace(hss_ctx* c, int nrhs) {
                                   wide ? lv.nwork_wide : lv.nwork, wide ? WIDE_ROWS_PER_WAVE : lv.rows_per_wave, lv.vec, nrhs,
                                   pool, lv.maxm);
     };
-    for (int l = L; l >= 1; --l) {
+    const int tl = c->top_l;
+    for (int l = L; l > tl; --l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
         HSS_TRY(sweep(lv, lv.up_items.as<SolveItem>()));
     }
-    HSS_TRY(sweep(c->lev[0], c->lev[0].up_items.as<SolveItem>()));
-    for (int l = 1; l <= L; ++l) {
+    if (tl == 0) {
+        HSS_TRY(sweep(c->lev[0], c->lev[0].up_items.as<SolveItem>()));
+    } else {
+        HSS_TRY(top_gemv_launch(st, c->topT.as<double>(), c->top_m, pool + (c->top_in - pool) * nrhs,
+                                pool + (c->top_out - pool) * nrhs, nrhs));
+    }
+    for (int l = tl + 1; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (lv.skip) continue;
         HSS_TRY(sweep(lv, lv.down_items.as<SolveItem>()));

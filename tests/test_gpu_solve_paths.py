@@ -1,0 +1,109 @@
+"""The two launch-saving devices of the solve / iteration against their plain forms (GPU only):
+  * "merge_top": the levels near the root replaced by one product with the inverse of the reduced matrix at a cut
+    level -- same solution to rounding as the level-by-level sweeps, both within 1e-10 of the oracle's ULV solve;
+  * "graph": two ADMM iterations replayed from a HIP graph -- bit-identical iterates to the eager launches, on
+    repeated runs with eager work between the replays."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import ulv as oulv            # noqa: E402
+from paper_2108_04167_amd import binding, synth   # noqa: E402
+
+
+def _dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+def _rel(a, b):
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+CASES = {
+    "cfg1": (1, 2048, 64, 128, {}),                       # whole tree merges into one operator (n <= 4096)
+    "cfg2_cut": (2, 8192, 128, 256, {}),
+    "cfg3_cut": (3, 16384, 256, 512, {}),
+    "ragged": (1, 4096, 32, 128, {"h": 20.0, "tol": 1e-5, "max_rank": 118}),   # tolerance-driven ranks, odd sizes
+    "two_leaves": (4, 64, 32, 128, {}),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_merged_top_equals_level_by_level(name):
+    from gpu_helpers import oracle_hss_from_export
+    cfg, n, leaf, s, over = CASES[name]
+    w = synth.make_workload(cfg, n=n, leaf=leaf, s=s)
+    over = dict(over)
+    max_rank = over.pop("max_rank", None)
+    for k, v in over.items():
+        setattr(w, k, v)
+    rng = np.random.default_rng(4)
+    B = rng.standard_normal((4, n))
+    sols, bytes_ = {}, {}
+    exp = None
+    for merge in (1, 0):
+        ctx = binding.Context()
+        ctx.hss_set_i64("merge_top", merge)
+        if max_rank:
+            ctx.hss_set_i64("max_rank", max_rank)
+        ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol, _dev(w.omega()))
+        ctx.hss_ulv_factor(w.beta)
+        X = _dev(B)
+        ctx.hss_ulv_solve(X)                      # four right-hand sides in one pass
+        x1 = _dev(B[2])
+        ctx.hss_ulv_solve(x1)                     # one of them alone
+        assert np.array_equal(X.cpu().numpy()[2], x1.cpu().numpy())
+        sols[merge] = X.cpu().numpy()
+        st = ctx.hss_stats()
+        bytes_[merge] = (st["factor_bytes"], st["factor_bytes_compact"])
+        if exp is None:
+            exp = ctx.hss_export()
+        ctx.close()
+    H = oracle_hss_from_export(exp)
+    Fz = oulv.ulv_factor(H, w.beta)
+    perm = exp["perm"]
+    for j in range(4):
+        ref = np.empty(n)
+        ref[perm] = oulv.ulv_solve(Fz, B[j][perm])
+        assert _rel(sols[1][j], ref) <= 1e-10 and _rel(sols[0][j], ref) <= 1e-10
+        assert _rel(sols[1][j], sols[0][j]) <= 1e-11
+    # level by level the solve reads the factors as stored; the compact count does not depend on the merge
+    assert bytes_[0][1] == bytes_[1][1] and bytes_[0][0] >= bytes_[0][1]
+    assert bytes_[1][0] > 0
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_cut", "ragged"])
+def test_graph_replay_gives_the_eager_iterates(name):
+    import torch
+    cfg, n, leaf, s, over = CASES[name]
+    w = synth.make_workload(cfg, n=n, leaf=leaf, s=s)
+    over = dict(over)
+    max_rank = over.pop("max_rank", None)
+    for k, v in over.items():
+        setattr(w, k, v)
+    ctx = binding.Context()
+    if max_rank:
+        ctx.hss_set_i64("max_rank", max_rank)
+    ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol, _dev(w.omega()))
+    ctx.hss_set_i64("graph", 0)
+    eager = {it: ctx.admm_svm_train(w.C, w.beta, it) for it in (16, 17, 61)}
+    ctx.hss_set_i64("graph", 1)
+    for rep in range(3):                         # replays interleaved with eager work and synchronisations
+        for it in (16, 17, 61):
+            out = ctx.admm_svm_train(w.C, w.beta, it)
+            for key in ("x", "z", "mu"):
+                assert torch.equal(out[key], eager[it][key]), (rep, it, key)
+            assert out["bias"] == eager[it]["bias"] and out["n_margin"] == eager[it]["n_margin"]
+        v = torch.randn(n, dtype=torch.float64, device="cuda:0")
+        ctx.hss_ulv_solve(v)
+        torch.cuda.synchronize()
+    # the lockstep C-sweep through the graph as well
+    Cs = [0.1, 1.0, 10.0]
+    multi = ctx.admm_svm_train_multi(Cs, w.beta, 40)
+    ctx.hss_set_i64("graph", 0)
+    for j, Cj in enumerate(Cs):
+        single = ctx.admm_svm_train(Cj, w.beta, 40)
+        assert torch.equal(multi["z"][j], single["z"]) and multi["bias"][j] == single["bias"]
+    ctx.close()
