@@ -69,8 +69,10 @@ def sweep(args, w, ctx, F, y):
     t_compress, _ = timed(lambda: ctx.hss_compress(F, y, w.h, w.leaf, w.tol))
     rows = []
     t_factor = t_lock = t_sep = 0.0
+    t_factor_each = []
     for beta in betas:
         tf, _ = timed(lambda: ctx.hss_ulv_factor(beta))
+        t_factor_each.append(tf)
         tl, multi = timed(lambda: ctx.admm_svm_train_multi(Cs, beta, w.maxit))
         ts = 0.0
         for j, Cj in enumerate(Cs):
@@ -89,6 +91,7 @@ def sweep(args, w, ctx, F, y):
            "config": {"workload": f"cfg{args.cfg}" + (f" cut to n={w.n}" if args.n else ""), "n": w.n, "r": w.r,
                       "h": w.h, "leaf": w.leaf, "sample_width": w.s, "C_grid": Cs, "beta_grid": betas,
                       "admm_iterations": w.maxit},
+           "factor_s_per_beta": t_factor_each,     # the first builds the beta-independent parts, the others reuse them
            "phases_s": {"compress": t_compress, "factor_all_betas": t_factor, "admm_lockstep_all_pairs": t_lock,
                         "admm_separate_runs_all_pairs": t_sep},
            "seconds_per_pair_lockstep": t_lock / npairs, "seconds_per_pair_separate": t_sep / npairs,

@@ -71,6 +71,11 @@ void hss_destroy(hss_ctx* ctx);
                            product with the inverse of the reduced matrix at the cut (chosen at factorization
                            time so that a solve takes the least modelled time; at most 4096 rows); 0: every
                            level is a launch of its own.  Set before hss_ulv_factor.
+        "cache_basis"      1 (default): the parts of the ULV factorization that depend on the generators only --
+                           the orthogonal change of basis of every node, the reduced bases, the parents'
+                           off-diagonal blocks -- are kept from the first factorization of a compression and
+                           reused by later ones with other beta (Sec. 3.2: what is computed once is reused
+                           across the grid); the factors are bit-identical either way.  0: recomputed every time.
         "graph"            1: admm_svm_train records two iterations (all launches of two ULV solves and two vector
                            updates) into a HIP graph and replays it, on a stream of the library's own that is
                            ordered after / before the context's stream by events; 0 (default): every launch is

@@ -29,6 +29,8 @@ struct Level {
     DevBuf Mup, Mdown;                      // dense operators of the up / down sweep
     std::vector<int64_t> kkoff;             // prefix sums of rk*rk
     DevBuf RT, RTi;                         // R^T and R^-T per node (k x k), R = reduced basis handed to the parent
+    DevBuf QT;                              // Q^T per eliminating node (m x m, at foff): depends on U only, kept across betas
+    DevBuf OffD;                            // R_a B R_b^T per inner node (k_a x k_b, at boff): likewise
     // solve plumbing
     double *bvec = nullptr, *ce = nullptr, *xvec = nullptr;   // level vectors inside hss_ctx::vpool (single-column
                                             // layout): input (sum msz), eliminated part (sum msz-rk), output (sum msz)
@@ -56,12 +58,14 @@ struct hss_ctx {
     hipEvent_t gevent = nullptr;            // orders gstream after / before the caller's stream
     // options
     int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
+    int64_t opt_cache_basis = 1;            // keep the beta-independent parts of the factorization between factorizations
     int64_t opt_graph = 0;                  // replay the ADMM iterations from a HIP graph (measured slower: off)
     int64_t opt_merge_top = 1;              // merge the top levels of the solve into one dense operator
     int64_t opt_adapt_start = 0, opt_adapt_step = 128;   // adaptive sample width: first width (0 = off), increment
     double  opt_abs_tol = 1e-8;
     // problem
     bool compressed = false, factored = false;
+    bool basis_cached = false;              // QT, RT, RTi, OffD of every level hold for the current compression
     int64_t n = 0, n_pad = 0;
     int r = 0, r_pad = 0, leaf = 0, L = 0, s = 0, s_pad = 0, kcap = 0;
     double h = 0.0, tol = 0.0, delta = 0.0, beta = -1.0;

@@ -268,7 +268,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     while ((int64_t(1) << L) < nl) ++L;
 
     hipStream_t st = c->stream;
-    c->compressed = c->factored = false;
+    c->compressed = c->factored = c->basis_cached = false;
     c->lev.clear();
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
@@ -645,7 +645,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
             }
     }
     hipStream_t st = c->stream;
-    c->compressed = c->factored = false;
+    c->compressed = c->factored = c->basis_cached = false;
     c->lev.clear();
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = 0; c->s_pad = 0; c->kcap = std::max(kmax, 1);

@@ -304,6 +304,12 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
         HSS_TRY(lv.Mdown.reserve(sizeof(double) * std::max<int64_t>(lv.foff[N], 1)));
         HSS_TRY(lv.RT.reserve(sizeof(double) * lv.kkoff[N]));
         HSS_TRY(lv.RTi.reserve(sizeof(double) * lv.kkoff[N]));
+        // The orthogonal change of basis Q of every node, the reduced bases R and the parents' off-diagonal
+        // blocks R_a B R_b^T depend on the generators U and B only, not on beta: they are kept from the first
+        // factorization of a compression and reused by every later one (caching across the grid, Sec. 3.2).
+        const bool cached = c->basis_cached;
+        HSS_TRY(lv.QT.reserve(sizeof(double) * std::max<int64_t>(lv.foff[N], 1)));
+        HSS_TRY(pl.OffD.reserve(sizeof(double) * std::max<int64_t>(pl.boff[pl.N], 1)));
         double* RT = lv.RT.as<double>();
         double* RTi = lv.RTi.as<double>();
         const double* Ug = lv.U.as<double>();
@@ -329,23 +335,24 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                 o_e[q + 1] = o_e[q] + e;
             }
             const size_t dsz = sizeof(double);
-            HSS_TRY(UT.reserve(dsz * std::max<int64_t>(o_km[nc], 1)));
-            HSS_TRY(PT0.reserve(dsz * std::max<int64_t>(o_em[nc], 1)));
-            if (!leaves) HSS_TRY(PT.reserve(dsz * std::max<int64_t>(o_em[nc], 1)));
-            HSS_TRY(G2.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
-            HSS_TRY(L2i.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
+            if (!cached) {
+                HSS_TRY(UT.reserve(dsz * std::max<int64_t>(o_km[nc], 1)));
+                HSS_TRY(PT0.reserve(dsz * std::max<int64_t>(o_em[nc], 1)));
+                if (!leaves) HSS_TRY(PT.reserve(dsz * std::max<int64_t>(o_em[nc], 1)));
+                HSS_TRY(G2.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
+                HSS_TRY(L2i.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
+                HSS_TRY(cholsc.reserve(dsz * (size_t)nc * 1024));
+            }
             HSS_TRY(E.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
             HSS_TRY(Einv.reserve(dsz * std::max<int64_t>(o_ee[nc], 1)));
-            HSS_TRY(QT.reserve(dsz * o_mm[nc]));
             HSS_TRY(Tmp.reserve(dsz * o_mm[nc]));
             HSS_TRY(Dh.reserve(dsz * o_mm[nc]));
             HSS_TRY(W.reserve(dsz * std::max<int64_t>(o_ke[nc], 1)));
             HSS_TRY(Wp.reserve(dsz * std::max<int64_t>(o_ke[nc], 1)));
             HSS_TRY(ipiv.reserve(sizeof(int) * std::max<int64_t>(o_e[nc], 1)));
-            HSS_TRY(cholsc.reserve(dsz * (size_t)nc * 1024));
 
             // ---- 1. UT = Uf^T = U^T blkdiag(R_a, R_b)^T for every node of the chunk ----
-            {
+            if (!cached) {
                 std::vector<CopyItem> ci;
                 std::vector<GemmItem> ga;
                 for (int q = 0; q < nc; ++q) {
@@ -371,14 +378,16 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                     const int t = t0 + q, m = lv.msz[t], k = lv.rk[t];
                     if (!lv.pass[t]) continue;
                     const double* U = Ug + lv.uoff[t];
-                    ci.push_back(cp(UT.as<double>() + o_km[q], RT + lv.kkoff[t], k, k, m, k, COPY_PLAIN));
-                    if (leaves) {
-                        ci.push_back(cp(U, RTi + lv.kkoff[t], k, k, k, k, COPY_PLAIN));
-                    } else {
-                        const int a = 2 * t, b = 2 * t + 1, ka = cl->rk[a], kb = cl->rk[b];
-                        ga.push_back(gi(cl->RTi.as<double>() + cl->kkoff[a], U, RTi + lv.kkoff[t], ka, k, ka, ka, k, k));
-                        ga.push_back(gi(cl->RTi.as<double>() + cl->kkoff[b], U + (size_t)ka * k,
-                                        RTi + lv.kkoff[t] + (size_t)ka * k, kb, k, kb, kb, k, k));
+                    if (!cached) {
+                        ci.push_back(cp(UT.as<double>() + o_km[q], RT + lv.kkoff[t], k, k, m, k, COPY_PLAIN));
+                        if (leaves) {
+                            ci.push_back(cp(U, RTi + lv.kkoff[t], k, k, k, k, COPY_PLAIN));
+                        } else {
+                            const int a = 2 * t, b = 2 * t + 1, ka = cl->rk[a], kb = cl->rk[b];
+                            ga.push_back(gi(cl->RTi.as<double>() + cl->kkoff[a], U, RTi + lv.kkoff[t], ka, k, ka, ka, k, k));
+                            ga.push_back(gi(cl->RTi.as<double>() + cl->kkoff[b], U + (size_t)ka * k,
+                                            RTi + lv.kkoff[t] + (size_t)ka * k, kb, k, kb, kb, k, k));
+                        }
                     }
                     const int i = t / 2, pm = pl.msz[i];
                     const int64_t offp = (t & 1) ? (int64_t)lv.rk[t - 1] * pm + lv.rk[t - 1] : 0;
@@ -394,7 +403,7 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
             if (!gen.empty()) {
                 double* pt0 = PT0.as<double>();
                 double* pt = leaves ? pt0 : PT.as<double>();
-                HIP_TRY(hipMemsetAsync(pt0, 0, dsz * o_em[nc], st));
+                if (!cached) HIP_TRY(hipMemsetAsync(pt0, 0, dsz * o_em[nc], st));
                 std::vector<CompItem> comp;
                 std::vector<GemmItem> gpt, gG1, gG2, gQ1, gQ2, gTmp, gDh, gW, gWp, gSch, gMu1, gMu2, gMd;
                 std::vector<CopyItem> cId1, cId2, cE, cDrr, cMu, cMd1, cMd2;
@@ -411,7 +420,7 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                     double* pp = pt + o_em[q];
                     double* g2 = G2.as<double>() + o_ee[q];
                     double* l2i = L2i.as<double>() + o_ee[q];
-                    double* qt = QT.as<double>() + o_mm[q];
+                    double* qt = lv.QT.as<double>() + lv.foff[t];
                     double* tmp = Tmp.as<double>() + o_mm[q];
                     double* dh = Dh.as<double>() + o_mm[q];
                     double* ee = E.as<double>() + o_ee[q];
@@ -459,18 +468,20 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                     cMd2.push_back(cp(qt + (size_t)k * m, md + k, m, e, m, m, COPY_TRANS));
                     gMd.push_back(gi(qt + (size_t)k * m, wp, md, m, k, e, m, k, m));
                 }
-                HSS_TRY(complement_launch(st, c->arena, comp));
-                HSS_TRY(bgemm_host(st, c->arena, gpt, false, true, 1.0, 0.0));
-                HSS_TRY(bgemm_host(st, c->arena, gG1, false, true, 1.0, 0.0));
-                HSS_TRY(bgemm_host(st, c->arena, gG2, false, true, 1.0, 0.0));
-                HSS_TRY(bchol(st, c->arena, ch1, cholsc.as<double>(), c->flags.as<int>() + 1));
-                HSS_TRY(bchol(st, c->arena, ch2, cholsc.as<double>(), c->flags.as<int>() + 1));
-                HSS_TRY(bcopy(st, c->arena, cId1));
-                HSS_TRY(bcopy(st, c->arena, cId2));
-                HSS_TRY(btrsm(st, c->arena, tr1, true, false));
-                HSS_TRY(btrsm(st, c->arena, tr2, true, false));
-                HSS_TRY(bgemm_host(st, c->arena, gQ1, false, false, 1.0, 0.0));
-                HSS_TRY(bgemm_host(st, c->arena, gQ2, false, false, 1.0, 0.0));
+                if (!cached) {      // Q^T = [L1^{-1} Uf^T; L2^{-1} P^T] and R^T = L1, R^{-T}: functions of U alone
+                    HSS_TRY(complement_launch(st, c->arena, comp));
+                    HSS_TRY(bgemm_host(st, c->arena, gpt, false, true, 1.0, 0.0));
+                    HSS_TRY(bgemm_host(st, c->arena, gG1, false, true, 1.0, 0.0));
+                    HSS_TRY(bgemm_host(st, c->arena, gG2, false, true, 1.0, 0.0));
+                    HSS_TRY(bchol(st, c->arena, ch1, cholsc.as<double>(), c->flags.as<int>() + 1));
+                    HSS_TRY(bchol(st, c->arena, ch2, cholsc.as<double>(), c->flags.as<int>() + 1));
+                    HSS_TRY(bcopy(st, c->arena, cId1));
+                    HSS_TRY(bcopy(st, c->arena, cId2));
+                    HSS_TRY(btrsm(st, c->arena, tr1, true, false));
+                    HSS_TRY(btrsm(st, c->arena, tr2, true, false));
+                    HSS_TRY(bgemm_host(st, c->arena, gQ1, false, false, 1.0, 0.0));
+                    HSS_TRY(bgemm_host(st, c->arena, gQ2, false, false, 1.0, 0.0));
+                }
                 HSS_TRY(bgemm_host(st, c->arena, gTmp, false, false, 1.0, 0.0));
                 HSS_TRY(bgemm_host(st, c->arena, gDh, false, true, 1.0, 0.0));
                 HSS_TRY(bcopy(st, c->arena, cE));
@@ -497,17 +508,22 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
             for (int i = 0; i < pl.N; ++i) o_t[i + 1] = o_t[i] + (int64_t)lv.rk[2 * i] * lv.rk[2 * i + 1];
             HSS_TRY(T1.reserve(sizeof(double) * std::max<int64_t>(o_t[pl.N], 1)));
             std::vector<GemmItem> g1(pl.N), g2(pl.N);
-            std::vector<CopyItem> ct(pl.N);
+            std::vector<CopyItem> cu(pl.N), ct(pl.N);
             for (int i = 0; i < pl.N; ++i) {
                 const int a = 2 * i, b = 2 * i + 1, ka = lv.rk[a], kb = lv.rk[b], pm = pl.msz[i];
                 double* t1 = T1.as<double>() + o_t[i];
+                double* off = pl.OffD.as<double>() + pl.boff[i];       // R_a B R_b^T (ka x kb), kept across betas
                 double* dp = Dn + pmm[i];
                 g1[i] = gi(RT + lv.kkoff[a], pl.B.as<double>() + pl.boff[i], t1, ka, kb, ka, ka, kb, kb);
-                g2[i] = gi(t1, RT + lv.kkoff[b], dp + ka, ka, kb, kb, kb, kb, pm);
-                ct[i] = cp(dp + ka, dp + (size_t)ka * pm, kb, ka, pm, pm, COPY_TRANS);
+                g2[i] = gi(t1, RT + lv.kkoff[b], off, ka, kb, kb, kb, kb, kb);
+                cu[i] = cp(off, dp + ka, ka, kb, kb, pm, COPY_PLAIN);
+                ct[i] = cp(off, dp + (size_t)ka * pm, kb, ka, kb, pm, COPY_TRANS);
             }
-            HSS_TRY(bgemm_host(st, c->arena, g1, true, false, 1.0, 0.0));
-            HSS_TRY(bgemm_host(st, c->arena, g2, false, false, 1.0, 0.0));
+            if (!cached) {
+                HSS_TRY(bgemm_host(st, c->arena, g1, true, false, 1.0, 0.0));
+                HSS_TRY(bgemm_host(st, c->arena, g2, false, false, 1.0, 0.0));
+            }
+            HSS_TRY(bcopy(st, c->arena, cu));
             HSS_TRY(bcopy(st, c->arena, ct));
             HIP_TRY(hipStreamSynchronize(st));
             c->arena.reset();
@@ -535,6 +551,7 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
     if (fl[0] || fl[1]) warn |= HSS_WPIVOT;
     c->warnings |= warn;
     c->beta = beta;
+    c->basis_cached = c->opt_cache_basis != 0;
     c->factor_bytes = bytes_solve;
     c->factor_bytes_compact = bytes_compact;
     c->factored = true;

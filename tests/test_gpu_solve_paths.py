@@ -107,3 +107,48 @@ def test_graph_replay_gives_the_eager_iterates(name):
         single = ctx.admm_svm_train(Cj, w.beta, 40)
         assert torch.equal(multi["z"][j], single["z"]) and multi["bias"][j] == single["bias"]
     ctx.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg3_cut", "ragged"])
+def test_cached_basis_gives_the_same_factors(name):
+    """Re-factorizations that reuse the beta-independent parts (Sec. 3.2, caching across the grid) against a
+    context that recomputes everything: solves and iterates bit-identical for every beta of a sweep."""
+    import torch
+    cfg, n, leaf, s, over = CASES[name]
+    w = synth.make_workload(cfg, n=n, leaf=leaf, s=s)
+    over = dict(over)
+    max_rank = over.pop("max_rank", None)
+    for k, v in over.items():
+        setattr(w, k, v)
+    ctxs = []
+    for cache in (1, 0):
+        ctx = binding.Context()
+        ctx.hss_set_i64("cache_basis", cache)
+        if max_rank:
+            ctx.hss_set_i64("max_rank", max_rank)
+        ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol, _dev(w.omega()))
+        ctxs.append(ctx)
+    b = torch.randn(n, dtype=torch.float64, device="cuda:0")
+    for beta in (0.5, 1.0, 2.0, 0.5):
+        res = []
+        for ctx in ctxs:
+            ctx.hss_ulv_factor(beta)
+            x = b.clone()
+            ctx.hss_ulv_solve(x)
+            out = ctx.admm_svm_train(w.C, beta, 10)
+            res.append((x, out))
+        assert torch.equal(res[0][0], res[1][0]), beta
+        for key in ("x", "z", "mu"):
+            assert torch.equal(res[0][1][key], res[1][1][key]), (beta, key)
+    # a new compression drops the cache
+    ctxs[0].hss_compress(_dev(w.F[::-1].copy()), _dev(w.y[::-1].copy()), w.h, w.leaf, w.tol, _dev(w.omega()))
+    ctxs[1].hss_compress(_dev(w.F[::-1].copy()), _dev(w.y[::-1].copy()), w.h, w.leaf, w.tol, _dev(w.omega()))
+    xs = []
+    for ctx in ctxs:
+        ctx.hss_ulv_factor(1.0)
+        x = b.clone()
+        ctx.hss_ulv_solve(x)
+        xs.append(x)
+    assert torch.equal(xs[0], xs[1])
+    for ctx in ctxs:
+        ctx.close()
