@@ -1,4 +1,6 @@
-"""Cluster tree by balanced coordinate bisection (oracle; test infrastructure).
+"""Cluster trees by balanced bisection (oracle; test infrastructure): along a coordinate
+(`cluster_tree`) or along the line between the two centres of a 2-means pass over the
+node (`cluster_tree_2means`, data-driven).
 
 The paper only says that the points are clustered/reordered before compression
 so that off-diagonal blocks become low-rank (Sec. 1.2, first bullet; Fig. 1).
@@ -38,6 +40,89 @@ def cluster_tree(F, leaf):
         c = int(np.flatnonzero(var >= var.max() * (1.0 - TIE))[0])
         order = np.lexsort((idx, sub[:, c]))     # primary key value, secondary original index
         idx = idx[order]
+        half = idx.size // 2
+        split(idx[:half])
+        split(idx[half:])
+
+    split(np.arange(n, dtype=np.int64))
+    return np.concatenate(out)
+
+
+QBITS = 38   # fixed-point bits of a feature value in the exact centre sums
+
+
+def _dist2(sub, c):
+    """Squared distances of the rows of `sub` to the point c, one feature after the
+    other in index order, every product and sum rounded on its own."""
+    d2 = np.zeros(sub.shape[0])
+    for f in range(sub.shape[1]):
+        diff = sub[:, f] - c[f]
+        d2 = d2 + diff * diff
+    return d2
+
+
+def cluster_tree_2means(F, leaf, iters=2):
+    """Data-driven cluster tree (the paper's clustering preprocess, Sec. 1.1 last
+    paragraph / Sec. 1.2 first bullet: the points are grouped so that off-diagonal
+    blocks of the kernel matrix get low rank).  Perfect binary tree as in
+    `cluster_tree`, but a node is split along the line between the two centres of a
+    2-means pass over its points instead of along a coordinate axis.
+
+    The rule is free of summation order, so that any implementation can reproduce
+    the permutation exactly:
+      * centres are means taken from EXACT integer sums of the features in fixed
+        point (value * 2^k rounded to the nearest integer, 2^k chosen from the largest
+        |feature| of the whole set so that |integer| <= 2^38), then
+        ((float)sum / (float)count) / 2^k;
+      * everything else is per point: squared distances and projections accumulated
+        feature by feature in index order with every operation rounded on its own,
+        compared or sorted across points, ties to the lowest original index.
+    Node rule:  c = mean of the node;  a = the point farthest from c;  b = the point
+    farthest from a;  centres (ca, cb) = (a, b);  `iters` times: points with
+    dist2(., ca) <= dist2(., cb) form A, the others B; stop if one is empty;
+    (ca, cb) = (mean A, mean B);  then sort the node by
+    (sum_f (x_f - ca_f) (cb_f - ca_f), original index), lower half -> left child.
+    """
+    F = np.asarray(F, dtype=np.float64)
+    n, r = F.shape
+    nl = n // leaf
+    if nl * leaf != n or nl & (nl - 1):
+        raise ValueError("n must be leaf * 2^L")
+    amax = float(np.abs(F).max()) if n else 0.0
+    if not np.isfinite(amax):
+        raise ValueError("non-finite feature")
+    e = np.frexp(amax)[1] if amax > 0 else 0           # amax < 2^e
+    scale = np.ldexp(1.0, QBITS - int(e))
+    Q = np.rint(F * scale).astype(np.int64)
+
+    def mean(rows):
+        return (Q[rows].sum(axis=0).astype(np.float64) / float(rows.size)) / scale
+
+    def farthest(idx, sub, c):
+        d2 = _dist2(sub, c)
+        cand = idx[d2 == d2.max()]
+        return int(cand.min())                          # ties -> lowest original index
+
+    out = []
+
+    def split(idx):
+        if idx.size == leaf:
+            out.append(idx)
+            return
+        sub = F[idx]
+        a = farthest(idx, sub, mean(idx))
+        b = farthest(idx, sub, F[a])
+        ca, cb = F[a].copy(), F[b].copy()
+        for _ in range(iters):
+            inA = _dist2(sub, ca) <= _dist2(sub, cb)
+            if inA.all() or not inA.any():
+                break
+            ca, cb = mean(idx[inA]), mean(idx[~inA])
+        d = cb - ca
+        p = np.zeros(idx.size)
+        for f in range(r):
+            p = p + (sub[:, f] - ca[f]) * d[f]
+        idx = idx[np.lexsort((idx, p))]
         half = idx.size // 2
         split(idx[:half])
         split(idx[half:])
