@@ -71,6 +71,14 @@ void hss_destroy(hss_ctx* ctx);
                            product with the inverse of the reduced matrix at the cut (chosen at factorization
                            time so that a solve takes the least modelled time; at most 4096 rows); 0: every
                            level is a launch of its own.  Set before hss_ulv_factor.
+        "clustering"       rule of the cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; always a perfect
+                           binary tree with equal-size nodes).  0 (default): a node is split at the median of
+                           the coordinate of largest variance.  1: data-driven -- along the line between the two
+                           centres of a 2-means pass over the node ("clustering_iterations" Lloyd steps, default
+                           2, started from the point farthest from the node's mean and the point farthest from
+                           that one), at the median of the projections.  The rule is free of summation order
+                           (centres from exact fixed-point sums, the rest per point), n < 2^24.
+        "clustering_iterations"
         "cache_basis"      1 (default): the parts of the ULV factorization that depend on the generators only --
                            the orthogonal change of basis of every node, the reduced bases, the parents'
                            off-diagonal blocks -- are kept from the first factorization of a compression and

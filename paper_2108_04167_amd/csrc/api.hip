@@ -53,6 +53,8 @@ int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
     else if (!strcmp(key, "psd_guard")) c->opt_guard = v ? 1 : 0;
     else if (!strcmp(key, "merge_top")) c->opt_merge_top = v ? 1 : 0;
     else if (!strcmp(key, "graph")) c->opt_graph = v ? 1 : 0;
+    else if (!strcmp(key, "clustering")) { if (v != 0 && v != 1) return HSS_EINVAL; c->opt_cluster = v; }
+    else if (!strcmp(key, "clustering_iterations")) { if (v < 0 || v > 64) return HSS_EINVAL; c->opt_cluster_iters = v; }
     else if (!strcmp(key, "cache_basis")) { c->opt_cache_basis = v ? 1 : 0; if (!v) c->basis_cached = false; }
     else if (!strcmp(key, "adaptive_start")) { if (v < 0) return HSS_EINVAL; c->opt_adapt_start = v; }
     else if (!strcmp(key, "adaptive_step")) { if (v < 1) return HSS_EINVAL; c->opt_adapt_step = v; }

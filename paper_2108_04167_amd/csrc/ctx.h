@@ -58,6 +58,7 @@ struct hss_ctx {
     hipEvent_t gevent = nullptr;            // orders gstream after / before the caller's stream
     // options
     int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
+    int64_t opt_cluster = 0, opt_cluster_iters = 2;   // cluster tree: 0 coordinate bisection, 1 two-means bisection
     int64_t opt_cache_basis = 1;            // keep the beta-independent parts of the factorization between factorizations
     int64_t opt_graph = 0;                  // replay the ADMM iterations from a HIP graph (measured slower: off)
     int64_t opt_merge_top = 1;              // merge the top levels of the solve into one dense operator
@@ -99,6 +100,8 @@ struct hss_ctx {
 };
 
 int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int64_t* perm_dev, int* bad_dev);
+int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int iters,
+                              int64_t* perm_dev, int* bad_dev);
 
 // noalloc.hip: device address of the library's fixed scratch array on the current device
 int noalloc_scratch_for_current_device(double** out);

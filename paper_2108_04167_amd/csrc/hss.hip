@@ -290,7 +290,11 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     std::vector<double> yh(n);
     HIP_TRY(hipMemcpyAsync(yh.data(), y, sizeof(double) * n, hipMemcpyDeviceToHost, st));
     HSS_TRY(c->perm.reserve(sizeof(int64_t) * n));
-    HSS_TRY(build_cluster_tree(st, F, n, r, leaf, c->perm.as<int64_t>(), c->flags.as<int>() + 3));
+    if (c->opt_cluster == 1)
+        HSS_TRY(build_cluster_tree_2means(st, F, n, r, leaf, (int)c->opt_cluster_iters, c->perm.as<int64_t>(),
+                                          c->flags.as<int>() + 3));
+    else
+        HSS_TRY(build_cluster_tree(st, F, n, r, leaf, c->perm.as<int64_t>(), c->flags.as<int>() + 3));
     c->perm_host.resize(n);
     int bad_f = 0;
     HIP_TRY(hipMemcpyAsync(c->perm_host.data(), c->perm.p, sizeof(int64_t) * n, hipMemcpyDeviceToHost, st));
