@@ -115,6 +115,10 @@ def main():
     ap.add_argument("--adaptive-step", type=int, default=128)
     ap.add_argument("--oversample", type=int, default=-1, help="oversampling p (rank cap = width - p; default width/2)")
     ap.add_argument("--max-rank", type=int, default=0)
+    ap.add_argument("--neighbours", action="store_true",
+                    help="neighbour-based sampling (the paper's own compressor) instead of the random sample K*Omega")
+    ap.add_argument("--ann-trees", type=int, default=3)
+    ap.add_argument("--clustering", type=int, default=0, help="cluster tree rule: 0 coordinate bisection, 1 two-means")
     ap.add_argument("--graph", action="store_true", help="replay the ADMM iterations from a HIP graph (A/B; default eager)")
     ap.add_argument("--no-merge-top", action="store_true", help="one launch per tree level in the solve (A/B)")
     ap.add_argument("--sweep", action="store_true",
@@ -152,6 +156,11 @@ def main():
         ctx.hss_set_i64("oversample", args.oversample)
     if args.max_rank:
         ctx.hss_set_i64("max_rank", args.max_rank)
+    if args.neighbours:
+        ctx.hss_set_i64("sampling", 1)
+        ctx.hss_set_i64("ann_trees", args.ann_trees)
+    if args.clustering:
+        ctx.hss_set_i64("clustering", args.clustering)
     if args.graph:
         ctx.hss_set_i64("graph", 1)
     if args.no_merge_top:
@@ -190,7 +199,7 @@ def main():
     t_solve_iter /= args.steps
     n, r, s = w.n, w.r, w.s
     flops = st["sample_flops"]        # 2 n^2 (columns + r) summed over the sampling launches of one compression
-    tf = flops / t_kernel / 1e12
+    tf = flops / t_kernel / 1e12 if t_kernel > 0 else 0.0
     solve_gbs = st2["factor_bytes"] / t_solve_iter / 1e9
 
     # one ULV solve alone: median of 64 back-to-back calls through the C ABI (permutation in and out included),
@@ -220,6 +229,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"cfg{args.cfg}" + (f" cut to n={n}" if args.n else ""), "n": n, "r": r, "h": w.h, "C": w.C, "leaf": w.leaf, "tol": w.tol,
+                   "sampling": "neighbours" if args.neighbours else "random", "clustering": args.clustering,
                    "sample_width": s, "sample_width_used": st["sample_width_used"], "rank_cap": st["rank_cap"],
                    "beta": w.beta, "admm_iterations": w.maxit},
         "phases_s": {"tree": st["t_tree"], "sampling": st["t_sample"], "levels": st["t_levels"], "guard": st["t_guard"],

@@ -71,6 +71,17 @@ void hss_destroy(hss_ctx* ctx);
                            product with the inverse of the reduced matrix at the cut (chosen at factorization
                            time so that a solve takes the least modelled time; at most 4096 rows); 0: every
                            level is a launch of its own.  Set before hss_ulv_factor.
+        "sampling"         how the off-diagonal block rows are sampled.  0 (default): random sample S = K Omega
+                           (randomized sampling, end of Sec. 3.2).  1: neighbour-based, the paper's own compressor
+                           (Sec. 3.1, first bullet): the sample of a node's block row is K(rows, N) with N the
+                           "sample_width" closest distinct approximate nearest neighbours of the node's row points
+                           that lie outside the node -- entries of K itself, no product with a random matrix and
+                           no O(n^2) work.  Neighbours: "ann_neighbours" k <= 64 per point (default 64) from
+                           "ann_trees" trees (default 3: the cluster-tree order plus random projection trees,
+                           directions from "seed") with exact search inside cells of "ann_cell" points (default
+                           512, rounded up to leaf * 2^j).  Ignored by hss_compress_with_samples; the adaptive
+                           width does not apply.  n < 2^31.
+        "ann_neighbours", "ann_cell", "ann_trees"
         "clustering"       rule of the cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; always a perfect
                            binary tree with equal-size nodes).  0 (default): a node is split at the median of
                            the coordinate of largest variance.  1: data-driven -- along the line between the two
@@ -225,6 +236,13 @@ int hss_stats(hss_ctx* ctx, hss_stats_t* out_host);
 int hss_export_sizes(hss_ctx* ctx, int64_t* nnodes, int64_t* u_len, int64_t* j_len, int64_t* b_len);
 int hss_export(hss_ctx* ctx, int64_t* perm, int32_t* sizes, int32_t* ranks, double* D, double* U,
                int32_t* J, double* B, double* delta_out);
+
+/* The neighbour lists of the last neighbour-based compression ("sampling" = 1), for tests and inspection:
+ * *k_out (host) = neighbours per point; idx_out (host, int32[n * k]) and dist_out (host, double[n * k]), either
+ * may be null: entry j of point i (points in cluster-tree order, i.e. point i is perm[i] of hss_export) is the
+ * cluster-tree index of its j-th neighbour and the squared distance to it, ascending by (distance, index), -1 /
+ * +infinity where fewer than k were found.  HSS_ESTATE without such a compression.  Synchronous. */
+int hss_export_neighbours(hss_ctx* ctx, int32_t* k_out, int32_t* idx_out, double* dist_out);
 
 /* The inverse of hss_export: puts the context into the compressed state from generators in HOST memory
  * (same arrays, same layout and node order as hss_export writes), for the points F_dev (n x r) and labels

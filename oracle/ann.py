@@ -95,24 +95,29 @@ def _merge_lists(idx_a, dist_a, idx_b, dist_b, k):
     return out_i, out_d
 
 
-def cells_of_projection_tree(F, cell, rng):
-    """Leaves (index arrays) of one random projection tree: a set is split at the median
-    of the projections of its points on a random direction until it holds at most
-    `cell` points."""
-    out = []
-    stack = [np.arange(F.shape[0], dtype=np.int64)]
-    while stack:
-        idx = stack.pop()
-        if idx.size <= cell:
-            out.append(idx)
-            continue
-        d = rng.standard_normal(F.shape[1])
-        p = F[idx] @ d
-        order = np.lexsort((idx, p))
-        half = idx.size // 2
-        stack.append(idx[order[half:]])
-        stack.append(idx[order[:half]])
-    return out
+def cells_of_projection_tree(F, cell, direction):
+    """Leaves (index arrays, left to right) of one random projection tree: a set is split at
+    the median of the projections of its points on a random direction until it holds at
+    most `cell` points.  direction(level, node) -> (r,) vector of the node-th set (left to
+    right) of a level.  A projection is accumulated feature by feature in index order,
+    every product and sum rounded on its own; ties go to the lowest index."""
+    r = F.shape[1]
+    level = [np.arange(F.shape[0], dtype=np.int64)]
+    l = 0
+    while level[0].size > cell:
+        nxt = []
+        for node, idx in enumerate(level):
+            d = direction(l, node)
+            p = np.zeros(idx.size)
+            for f in range(r):
+                p = p + F[idx, f] * d[f]
+            order = np.lexsort((idx, p))
+            half = idx.size // 2
+            nxt.append(idx[order[:half]])
+            nxt.append(idx[order[half:]])
+        level = nxt
+        l += 1
+    return level
 
 
 def knn_in_cells(F, cells, k):
@@ -127,16 +132,21 @@ def knn_in_cells(F, cells, k):
     return idx, dist
 
 
-def ann_projection_trees(F, k, cell, trees, seed=0):
+def ann_projection_trees(F, k, cell, trees, seed=0, directions=None):
     """Approximate k nearest neighbours: tree 0 = contiguous runs of `cell` points in the
     given order (for points in cluster-tree order: the cells of that tree), trees
-    1 .. trees-1 = random projection trees; exact search inside every cell; lists merged."""
+    1 .. trees-1 = random projection trees; exact search inside every cell; lists merged.
+    directions(tree, level, node) -> (r,) supplies the random directions (default: normal
+    numbers from a generator seeded with `seed`)."""
     n = F.shape[0]
-    rng = np.random.default_rng(seed)
+    if directions is None:
+        rng = np.random.default_rng(seed)
+        directions = lambda t, l, node: rng.standard_normal(F.shape[1])
     cells = [np.arange(i, min(n, i + cell), dtype=np.int64) for i in range(0, n, cell)]
     idx, dist = knn_in_cells(F, cells, k)
-    for _ in range(1, trees):
-        i2, d2 = knn_in_cells(F, cells_of_projection_tree(F, cell, rng), k)
+    for t in range(1, trees):
+        tree_cells = cells_of_projection_tree(F, cell, lambda l, node: directions(t, l, node))
+        i2, d2 = knn_in_cells(F, tree_cells, k)
         idx, dist = _merge_lists(idx, dist, i2, d2, k)
     return idx, dist
 

@@ -52,6 +52,7 @@ ABI = {
     "hss_stats": (C.c_int, [C.c_void_p, C.POINTER(HssStats)]),
     "hss_export_sizes": (C.c_int, [C.c_void_p] + [C.POINTER(C.c_int64)] * 4),
     "hss_export": (C.c_int, [C.c_void_p, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, C.POINTER(C.c_double)]),
+    "hss_export_neighbours": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), c_dp, c_dp]),
     "hss_import": (C.c_int, [C.c_void_p, c_dp, c_dp, C.c_int64, C.c_int32, C.c_double, C.c_int32,
                              c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, c_dp, C.c_double]),
 }
@@ -235,6 +236,17 @@ class Context:
         return {"n": n, "leaf": leaf, "perm": perm, "sizes": sizes, "ranks": ranks,
                 "D": D.reshape(n // leaf, leaf, leaf), "U": U[:ul.value], "J": J[:jl.value], "B": B[:bl.value],
                 "delta": delta.value}
+
+    def hss_export_neighbours(self):
+        """(idx, dist) of the last neighbour-based compression: (n, k) int32 / float64, cluster-tree order."""
+        import numpy as np
+        k = C.c_int32(0)
+        _check(_lib.hss_export_neighbours(self._h, C.byref(k), None, None), "hss_export_neighbours")
+        idx = np.empty((self.n, k.value), dtype=np.int32)
+        dist = np.empty((self.n, k.value), dtype=np.float64)
+        _check(_lib.hss_export_neighbours(self._h, C.byref(k), C.c_void_p(idx.ctypes.data), C.c_void_p(dist.ctypes.data)),
+               "hss_export_neighbours")
+        return idx, dist
 
     def hss_import(self, F, y, h, leaf, gen):
         """Compressed state from host generators `gen` (a dict laid out like hss_export's result)."""

@@ -53,6 +53,10 @@ int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
     else if (!strcmp(key, "psd_guard")) c->opt_guard = v ? 1 : 0;
     else if (!strcmp(key, "merge_top")) c->opt_merge_top = v ? 1 : 0;
     else if (!strcmp(key, "graph")) c->opt_graph = v ? 1 : 0;
+    else if (!strcmp(key, "sampling")) { if (v != 0 && v != 1) return HSS_EINVAL; c->opt_sampling = v; }
+    else if (!strcmp(key, "ann_neighbours")) { if (v < 1 || v > 64) return HSS_EINVAL; c->opt_ann_k = v; }
+    else if (!strcmp(key, "ann_cell")) { if (v < 2 || v > (1 << 20)) return HSS_EINVAL; c->opt_ann_cell = v; }
+    else if (!strcmp(key, "ann_trees")) { if (v < 1 || v > 64) return HSS_EINVAL; c->opt_ann_trees = v; }
     else if (!strcmp(key, "clustering")) { if (v != 0 && v != 1) return HSS_EINVAL; c->opt_cluster = v; }
     else if (!strcmp(key, "clustering_iterations")) { if (v < 0 || v > 64) return HSS_EINVAL; c->opt_cluster_iters = v; }
     else if (!strcmp(key, "cache_basis")) { c->opt_cache_basis = v ? 1 : 0; if (!v) c->basis_cached = false; }
@@ -329,6 +333,18 @@ int hss_stream_copy(hss_ctx* c, const double* src, double* dst, int64_t n) {
     if (!c || !src || !dst || n < 2 || (n & 1)) return HSS_EINVAL;
     if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return HSS_EINVAL;
     return stream_copy_launch(c->stream, src, dst, n);
+}
+
+int hss_export_neighbours(hss_ctx* c, int32_t* k_out, int32_t* idx_out, double* dist_out) {
+    if (!c || !k_out) return HSS_EINVAL;
+    if (!c->compressed || c->ann_k <= 0 || !c->nbr_idx.p) return HSS_ESTATE;
+    *k_out = c->ann_k;
+    if (!idx_out && !dist_out) return HSS_OK;
+    const size_t cnt = (size_t)c->n * c->ann_k;
+    if (idx_out) HIP_TRY(hipMemcpyAsync(idx_out, c->nbr_idx.p, sizeof(int32_t) * cnt, hipMemcpyDeviceToHost, c->stream));
+    if (dist_out) HIP_TRY(hipMemcpyAsync(dist_out, c->nbr_dist.p, sizeof(double) * cnt, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return HSS_OK;
 }
 
 int hss_stats(hss_ctx* c, hss_stats_t* o) {

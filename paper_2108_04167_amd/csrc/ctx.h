@@ -58,6 +58,8 @@ struct hss_ctx {
     hipEvent_t gevent = nullptr;            // orders gstream after / before the caller's stream
     // options
     int64_t opt_s = 128, opt_p = -1, opt_max_rank = 0, opt_seed = 0, opt_guard = 1;   // opt_p < 0: s/2
+    int64_t opt_sampling = 0;               // 0: random sample K Omega; 1: columns of approximate nearest neighbours
+    int64_t opt_ann_k = 64, opt_ann_cell = 512, opt_ann_trees = 3;
     int64_t opt_cluster = 0, opt_cluster_iters = 2;   // cluster tree: 0 coordinate bisection, 1 two-means bisection
     int64_t opt_cache_basis = 1;            // keep the beta-independent parts of the factorization between factorizations
     int64_t opt_graph = 0;                  // replay the ADMM iterations from a HIP graph (measured slower: off)
@@ -74,6 +76,8 @@ struct hss_ctx {
     int width_used = 0;                     // sample columns the decompositions ended up using
     int64_t nodes_redone = 0;               // node decompositions repeated after widening the sample
     DevBuf Fp, nu, yp, perm, Dleaf;
+    DevBuf nbr_idx, nbr_dist;               // neighbour lists (n x ann_k, cluster-tree order), neighbour-based sampling
+    int ann_k = 0;
     std::vector<int64_t> perm_host;
     std::vector<Level> lev;                 // 0 .. L
     DevBuf rootinv;                         // inverse of the root block (root_m x root_m)
@@ -105,6 +109,11 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
 
 // noalloc.hip: device address of the library's fixed scratch array on the current device
 int noalloc_scratch_for_current_device(double** out);
+// ann.hip
+int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed);
+int ann_select_columns(hss_ctx* c, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host, int64_t rows, int N,
+                       int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host);
+double ann_direction_component(uint64_t seed, int tree, int level, int64_t node, int f);
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
                       const double* Omega, int s_in);

@@ -253,7 +253,8 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     if (!gram_id && s_pad > 1024) return HSS_EUNSUPPORTED;
     // Adaptive sample width (option "adaptive_start" > 0): the decompositions first see `width` columns; the rank
     // cap at width w is w - p(w), never above the final cap.
-    const bool adaptive = c->opt_adapt_start > 0 && c->opt_adapt_start < s;
+    const bool ann = c->opt_sampling == 1 && !Omega;       // neighbour-based sample instead of K Omega
+    const bool adaptive = !ann && c->opt_adapt_start > 0 && c->opt_adapt_start < s;
     const int step = (int)c->opt_adapt_step;
     if (adaptive && (s % 128 || c->opt_adapt_start % 128 || step < 128 || step % 128)) return HSS_EINVAL;
     auto cap_at = [&](int64_t w) { return w - (c->opt_p >= 0 ? c->opt_p : w / 2); };
@@ -274,6 +275,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
     c->h = h; c->tol = tol; c->delta = 0.0; c->beta = -1.0; c->warnings = 0;
     c->width_used = width; c->nodes_redone = 0;
+    c->ann_k = 0;
     c->r_pad = feature_pad(r);
     c->n_pad = round_up(n, 256);
     const int r_pad = c->r_pad;
@@ -324,7 +326,9 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     HSS_TRY(Sb[0].reserve(nsbytes));
     HSS_TRY(Ob[0].reserve(nsbytes));
     t0 = wall();
-    if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Ob[0].as<double>(), n, n_pad, s, s_pad));
+    if (ann) {
+        HSS_TRY(ann_search(c, (int)c->opt_ann_k, (int)c->opt_ann_cell, (int)c->opt_ann_trees, (uint64_t)c->opt_seed));
+    } else if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Ob[0].as<double>(), n, n_pad, s, s_pad));
     else HSS_TRY(omega_fill_launch(st, Ob[0].as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
     c->t_sample_kernel = 0.0;
     c->sample_flops = 0.0;
@@ -355,7 +359,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         c->sample_flops += 2.0 * (double)n * (double)n * (double)((c1 - c0) + r);
         return HSS_OK;
     };
-    HSS_TRY(sample_columns(0, width));
+    if (!ann) HSS_TRY(sample_columns(0, width));
     c->t_sample = wall() - t0;
 
     // ---- leaf level: D_t and S_t = S - D Omega ----
@@ -383,13 +387,17 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
             kb[t] = KBItem{nullptr, nullptr, (int64_t)t * leaf, (int64_t)t * leaf,
                            c->Dleaf.as<double>() + (size_t)t * leaf * leaf, leaf, leaf, leaf, 0};
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
-        if (L >= 1) HSS_TRY(leaf_columns(0, width));
+        if (L >= 1 && !ann) HSS_TRY(leaf_columns(0, width));
     }
     if (L >= 1) {
-        HSS_TRY(Sb[1].reserve(nsbytes));
-        HSS_TRY(Ob[1].reserve(nsbytes));
+        if (!ann) {
+            HSS_TRY(Sb[1].reserve(nsbytes));
+            HSS_TRY(Ob[1].reserve(nsbytes));
+        }
         if (!gram_id) HSS_TRY(Wk.reserve(nsbytes));
     }
+    DevBuf ann_cols;                         // sample columns of the nodes of a level (N x s point indices)
+    if (ann && L >= 1) HSS_TRY(ann_cols.reserve(sizeof(int64_t) * (size_t)nl * s));
     const int kc = (int)kcap;
     DevBuf Lc, norms0, norms1, sel, jtmp, rkd, done, r11, Gm, d_goff, d_active;
     if (L >= 1) {
@@ -441,9 +449,23 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         Level& lv = c->lev[l];
         const int N = lv.N;
         const int64_t rows = lv.moff[N];
-        const int pc = (L - l) & 1;
+        const int pc = ann ? 0 : (L - l) & 1;
         double* Acur = Sb[pc].as<double>();
         HSS_TRY(upload(c, lv.d_moff, lv.moff));
+        if (ann) {
+            // the level's sample blocks S_t = K(rows of t, columns of the nearest outside neighbours of those rows)
+            std::vector<int32_t> rownode((size_t)rows), ncols;
+            for (int t = 0; t < N; ++t)
+                for (int64_t q = lv.moff[t]; q < lv.moff[t + 1]; ++q) rownode[(size_t)q] = t;
+            const int64_t* rowpoint = l == L ? nullptr : c->lev[l + 1].skel.as<int64_t>();
+            HSS_TRY(ann_select_columns(c, rowpoint, rownode, rows, N, n >> l, s, ann_cols.as<int64_t>(), ncols));
+            HSS_TRY(fill_launch(st, Acur, rows * (int64_t)LD, 0.0));
+            std::vector<KBItem> kb(N);
+            for (int t = 0; t < N; ++t)
+                kb[t] = KBItem{rowpoint ? rowpoint + lv.moff[t] : nullptr, ann_cols.as<int64_t>() + (size_t)t * s, lv.moff[t], 0,
+                               Acur + (size_t)lv.moff[t] * LD, lv.msz[t], ncols[t], LD, 0};
+            HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
+        }
         // interpolative decompositions of the nodes of the level; with the adaptive width, again for the nodes
         // that the sample's rank cap cut, after widening the sample
         IdLevelArgs ia;
@@ -559,7 +581,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
                            pl.B.as<double>() + pl.boff[i], lv.rk[a], lv.rk[b], lv.rk[b], 0};
         }
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
-        if (l - 1 >= 1) HSS_TRY(push_columns(l, 0, width));
+        if (l - 1 >= 1 && !ann) HSS_TRY(push_columns(l, 0, width));
     }
     if (status < 0) return status;
     c->width_used = width;
