@@ -17,9 +17,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 FP64_MFMA_PEAK_TFLOPS = 78.6
-# (workload, n) -> HBM bytes per launch (sample_kernel) / per solve (all solve_gemv_kernel launches of one solve),
-# read + written, from profiles/sample_kernel_cfg3_counters.txt and profiles/solve_gemv_kernel_cfg3_counters.txt.
-MEASURED_TRAFFIC_BYTES = {(3, 262144): {"sample_kernel": 7.627e11, "solve": 4.388e9}}
+# (workload, n) -> HBM bytes per launch (sample_kernel) / per solve (all launches of one ULV solve), read + written,
+# from the FETCH_SIZE / WRITE_SIZE counter runs summarised in profiles/sample_kernel_cfg3_counters.txt and
+# profiles/solve_gemv_kernel_cfg3_counters.txt, each with the SHA-256 (first 16 hex digits) of the kernel source the
+# counters were taken on: a figure is reported only while that source is unchanged, null otherwise.
+MEASURED_TRAFFIC_BYTES = {(3, 262144): {"sample_kernel": (8.219e11, "sample.hip", "a5eef59bd2f1875b"),
+                                        "solve": (4.393e9, "solve.hip", "9b26fe6d70520f64")}}
+
+
+def measured_traffic(cfg, n, which):
+    import hashlib
+    ent = MEASURED_TRAFFIC_BYTES.get((cfg, n), {}).get(which)
+    if ent is None:
+        return None, "no counter run for this workload"
+    nbytes, src, sha = ent
+    path = os.path.join(ROOT, "paper_2108_04167_amd", "csrc", src)
+    cur = hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+    if cur != sha:
+        return None, f"{src} changed since the counters were taken (profiles/): retake them"
+    return nbytes, f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on {src} {sha}, see profiles/"
 
 
 def cpu_baseline(cfg, n_small, maxit):
@@ -109,6 +125,7 @@ def main():
     ap.add_argument("--copy-probe", type=int, default=0,
                     help="also run one plain device-to-device copy of this many bytes (reference for HBM counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-neighbour-leg", action="store_true", help="skip the extra pass with neighbour-based sampling")
     ap.add_argument("--sample-width", type=int, default=0, help="override the workload's sample width s (largest width "
                     "with --adaptive-start)")
     ap.add_argument("--adaptive-start", type=int, default=0, help="adaptive sample width: first width (0 = off)")
@@ -220,7 +237,9 @@ def main():
 
     # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by
     # a plain copy of known size); they hold for the default workload and the kernels they were taken on only.
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.cfg, n), {})
+    default_path = not (args.neighbours or args.sample_width or args.adaptive_start or args.no_merge_top)
+    tr_sample, note_sample = measured_traffic(args.cfg, n, "sample_kernel") if default_path else (None, "non-default options")
+    tr_solve, note_solve = measured_traffic(args.cfg, n, "solve") if default_path else (None, "non-default options")
 
     rel_err = ctx.hss_error_estimate(8, 1)     # achieved ||K~ - K||_F / ||K||_F on 8 probe vectors (not timed)
 
@@ -236,16 +255,37 @@ def main():
                      "factor": st2["t_factor"], "admm_and_bias": t_train - st2["t_factor"]},
         "roofline": {"kernel": "sample_kernel (S = K*Omega, fused Gram+exp+contraction)", "bound": "mfma",
                      "achieved": tf, "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / FP64_MFMA_PEAK_TFLOPS,
-                     "traffic": traffic.get("sample_kernel"), "flops_per_launch": flops, "seconds_per_launch": t_kernel},
+                     "traffic": tr_sample, "traffic_source": note_sample, "flops_per_launch": flops,
+                     "seconds_per_launch": t_kernel},
         "roofline_solve": {"kernel": "solve_gemv_kernel (ULV up/down sweeps, per ADMM iteration incl. vector update)",
                            "bound": "hbm", "achieved": solve_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": solve_gbs / HBM_PEAK_GBS, "traffic": traffic.get("solve"),
+                           "frac": solve_gbs / HBM_PEAK_GBS, "traffic": tr_solve, "traffic_source": note_solve,
                            "bytes_per_solve": st2["factor_bytes"], "bytes_per_solve_compact": st2["factor_bytes_compact"],
                            "seconds_per_iteration": t_solve_iter, "seconds_per_solve_median_of_64": t_solve_median},
         "model": {"delta": st["delta"], "rank_max": st["rank_max"], "nodes_at_cap": st["nodes_at_cap"],
                   "rel_error_estimate": rel_err, "tolerance_met": bool(rel_err <= w.tol and st["nodes_at_cap"] == 0),
                   "bias": out["bias"], "n_margin": out["n_margin"], "test_accuracy_pct": acc, "warnings": st2["warnings"]},
     }
+    if not args.neighbours and not args.no_neighbour_leg:
+        # the same train with the paper's own neighbour-based sample in place of K*Omega (one pass, not the metric)
+        ctx2 = binding.Context()
+        ctx2.hss_set_i64("sample_width", w.s)
+        ctx2.hss_set_i64("sampling", 1)
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx2.hss_compress(F, y, w.h, w.leaf, w.tol)
+            o2 = ctx2.admm_svm_train(w.C, w.beta, w.maxit)
+            torch.cuda.synchronize()
+            t_ann = time.perf_counter() - t0
+        s2 = ctx2.hss_stats()
+        dec2 = ctx2.svm_decision(torch.tensor(w.F_test, device=dev), o2["z"], o2["bias"])
+        acc2 = float((((dec2 >= 0).double() * 2 - 1) == torch.tensor(w.y_test, device=dev)).double().mean().item() * 100)
+        rec["neighbour_sampling"] = {"train_seconds": t_ann, "rel_error_estimate": ctx2.hss_error_estimate(8, 1),
+                                     "delta": s2["delta"], "test_accuracy_pct": acc2,
+                                     "note": "option sampling=1 (Sec. 3.1 of the paper: columns of approximate nearest "
+                                             "neighbours instead of the random sample); same width and rank cap"}
+        ctx2.close()
     if not args.no_cpu_baseline:
         n_small = min(n, 4096 if args.cfg != 1 else 2048)
         cb = cpu_baseline(args.cfg, n_small, w.maxit)
