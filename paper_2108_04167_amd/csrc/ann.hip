@@ -338,12 +338,13 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
 // Sample columns of the N nodes of a level.  rowpoint: point behind each of the level's `rows` rows (null: row q is
 // point q, the leaf level); rownode_host: node of each row; width: points under a node.  cols_dev: N x s point
 // indices; ncols_host: how many of them each node has.
-int ann_select_columns(hss_ctx* c, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host, int64_t rows, int N,
-                       int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host) {
+int ann_select_columns(hss_ctx* c, AnnWork& wk, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host,
+                       int64_t rows, int N, int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host) {
     hipStream_t st = c->stream;
     const int k = c->ann_k;
     const int64_t count = rows * k;
-    DevBuf rn, keys_a, keys_b, tmp, seg_lo, seg_hi, ncd;
+    DevBuf &rn = wk.rn, &keys_a = wk.keys_a, &keys_b = wk.keys_b, &tmp = wk.tmp, &seg_lo = wk.seg_lo, &seg_hi = wk.seg_hi,
+           &ncd = wk.ncd;      // grown on demand, reused by every level of a compression
     HSS_TRY(rn.reserve(sizeof(int32_t) * (size_t)rows));
     HSS_TRY(keys_a.reserve(sizeof(CKey) * (size_t)count));
     HSS_TRY(keys_b.reserve(sizeof(CKey) * (size_t)count));
@@ -372,6 +373,6 @@ int ann_select_columns(hss_ctx* c, const int64_t* rowpoint, const std::vector<in
     HIP_TRY(hipGetLastError());
     ncols_host.resize(N);
     HIP_TRY(hipMemcpyAsync(ncols_host.data(), ncd.p, sizeof(int32_t) * (size_t)N, hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));                // also keeps the work buffers alive until the kernels are done
+    HIP_TRY(hipStreamSynchronize(st));                // ncols_host is read by the caller right away
     return HSS_OK;
 }

@@ -111,8 +111,11 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
 int noalloc_scratch_for_current_device(double** out);
 // ann.hip
 int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed);
-int ann_select_columns(hss_ctx* c, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host, int64_t rows, int N,
-                       int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host);
+struct AnnWork {    // work buffers of ann_select_columns, reused across the levels of one compression
+    DevBuf rn, keys_a, keys_b, tmp, seg_lo, seg_hi, ncd;
+};
+int ann_select_columns(hss_ctx* c, AnnWork& wk, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host,
+                       int64_t rows, int N, int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host);
 double ann_direction_component(uint64_t seed, int tree, int level, int64_t node, int f);
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,

@@ -324,7 +324,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     const size_t nsbytes = sizeof(double) * (size_t)n_pad * s_pad;
     const int LD = s_pad;
     HSS_TRY(Sb[0].reserve(nsbytes));
-    HSS_TRY(Ob[0].reserve(nsbytes));
+    if (!ann) HSS_TRY(Ob[0].reserve(nsbytes));
     t0 = wall();
     if (ann) {
         HSS_TRY(ann_search(c, (int)c->opt_ann_k, (int)c->opt_ann_cell, (int)c->opt_ann_trees, (uint64_t)c->opt_seed));
@@ -396,6 +396,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         }
         if (!gram_id) HSS_TRY(Wk.reserve(nsbytes));
     }
+    AnnWork ann_work;
     DevBuf ann_cols;                         // sample columns of the nodes of a level (N x s point indices)
     if (ann && L >= 1) HSS_TRY(ann_cols.reserve(sizeof(int64_t) * (size_t)nl * s));
     const int kc = (int)kcap;
@@ -458,7 +459,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
             for (int t = 0; t < N; ++t)
                 for (int64_t q = lv.moff[t]; q < lv.moff[t + 1]; ++q) rownode[(size_t)q] = t;
             const int64_t* rowpoint = l == L ? nullptr : c->lev[l + 1].skel.as<int64_t>();
-            HSS_TRY(ann_select_columns(c, rowpoint, rownode, rows, N, n >> l, s, ann_cols.as<int64_t>(), ncols));
+            HSS_TRY(ann_select_columns(c, ann_work, rowpoint, rownode, rows, N, n >> l, s, ann_cols.as<int64_t>(), ncols));
             HSS_TRY(fill_launch(st, Acur, rows * (int64_t)LD, 0.0));
             std::vector<KBItem> kb(N);
             for (int t = 0; t < N; ++t)

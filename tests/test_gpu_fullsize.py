@@ -91,12 +91,14 @@ def _bias_and_labels(ctx, w, out, oref, H, perm, name, n_test=512):
     assert abs(oadmm.accuracy(dec, w.y_test[:n_test]) - oadmm.accuracy(dec_ref, w.y_test[:n_test])) <= 0.1
 
 
-def _stage_compress(w, check_guard=False, sample_rows=16):
+def _stage_compress(w, check_guard=False, sample_rows=16, options=None):
     """Sampled rows of S, compression with the in-library Omega (the benchmark's path), export, tree and one
     leaf block against the oracle.  Returns the state the later stages work on."""
     from gpu_helpers import oracle_hss_from_export
     ctx = binding.Context()
     ctx.hss_set_i64("sample_width", w.s)
+    for key, val in (options or {}).items():
+        ctx.hss_set_i64(key, val)
     F, y = _dev(w.F), _dev(w.y)
     if sample_rows:
         Om = _library_omega(w.n, w.s)
@@ -163,6 +165,35 @@ def _full_oracle_parity(w, admm_iters, check_guard=False):
     _stage_solve(st)
     _stage_admm(st, admm_iters)
     st["ctx"].close()
+
+
+def test_cfg3_full_size_neighbour_based_against_oracle():
+    """Workload 3 at full size compressed from the neighbour-based sample (Sec. 3.1, first bullet): the exported
+    matrix through the oracle's ULV factorization, solve, mat-vec, ADMM, bias and labels like the random sample's."""
+    st = _stage_compress(synth.make_workload(3), sample_rows=0, options={"sampling": 1})
+    assert st["stats"]["sample_flops"] == 0.0                # no product with a random matrix was formed
+    _stage_solve(st)
+    _stage_admm(st, 6)
+    st["ctx"].close()
+
+
+def test_cfg2_full_size_neighbour_lists_against_oracle():
+    """The neighbour lists of workload 2 at full size (65 536 points, 64 neighbours each, three trees) against the
+    oracle's search with the library's random directions: identical indices, bit-identical distances."""
+    from oracle import ann as oann
+    from test_gpu_ann import _library_directions
+    w = synth.make_workload(2)
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", w.s)
+    ctx.hss_set_i64("sampling", 1)
+    ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, w.leaf, w.tol)
+    idx, dist = ctx.hss_export_neighbours()
+    perm = ctx.hss_export()["perm"]
+    ctx.close()
+    _say("cfg2: oracle neighbour search")
+    ref_i, ref_d = oann.ann_projection_trees(w.F[perm], 64, 512, 3, directions=_library_directions(0, w.r))
+    assert np.array_equal(idx, ref_i)
+    assert np.array_equal(dist, ref_d)
 
 
 def test_cfg2_full_size_against_oracle():
