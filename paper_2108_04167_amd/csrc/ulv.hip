@@ -401,8 +401,8 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
             for (int q = 0; q < nc; ++q)
                 if (!lv.pass[t0 + q]) gen.push_back(q);
             if (!gen.empty()) {
-                double* pt0 = PT0.as<double>();
-                double* pt = leaves ? pt0 : PT.as<double>();
+                double* pt0 = cached ? nullptr : PT0.as<double>();
+                double* pt = cached ? nullptr : (leaves ? pt0 : PT.as<double>());
                 if (!cached) HIP_TRY(hipMemsetAsync(pt0, 0, dsz * o_em[nc], st));
                 std::vector<CompItem> comp;
                 std::vector<GemmItem> gpt, gG1, gG2, gQ1, gQ2, gTmp, gDh, gW, gWp, gSch, gMu1, gMu2, gMd;
@@ -415,11 +415,6 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                     const int t = t0 + q, m = lv.msz[t], k = lv.rk[t], e = m - k;
                     const double* U = Ug + lv.uoff[t];
                     const int* J = lv.J.as<int>() + lv.koff[t];
-                    double* ut = UT.as<double>() + o_km[q];
-                    double* p0 = pt0 + o_em[q];
-                    double* pp = pt + o_em[q];
-                    double* g2 = G2.as<double>() + o_ee[q];
-                    double* l2i = L2i.as<double>() + o_ee[q];
                     double* qt = lv.QT.as<double>() + lv.foff[t];
                     double* tmp = Tmp.as<double>() + o_mm[q];
                     double* dh = Dh.as<double>() + o_mm[q];
@@ -432,22 +427,29 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
                     double* mu = lv.Mup.as<double>() + lv.foff[t];
                     double* md = lv.Mdown.as<double>() + lv.foff[t];
                     const double* D = Dc + mm[t];
-                    comp.push_back(CompItem{U, J, p0, m, k, m, 0});
-                    if (!leaves) {
-                        const int a = 2 * t, b = 2 * t + 1, ka = cl->rk[a], kb = cl->rk[b];
-                        gpt.push_back(gi(p0, cl->RTi.as<double>() + cl->kkoff[a], pp, e, ka, ka, m, ka, m));
-                        gpt.push_back(gi(p0 + ka, cl->RTi.as<double>() + cl->kkoff[b], pp + ka, e, kb, kb, m, kb, m));
+                    if (!cached) {      // the items that build Q^T, R^T, R^-T (their work buffers exist only then)
+                        double* ut = UT.as<double>() + o_km[q];
+                        double* p0 = pt0 + o_em[q];
+                        double* pp = pt + o_em[q];
+                        double* g2 = G2.as<double>() + o_ee[q];
+                        double* l2i = L2i.as<double>() + o_ee[q];
+                        comp.push_back(CompItem{U, J, p0, m, k, m, 0});
+                        if (!leaves) {
+                            const int a = 2 * t, b = 2 * t + 1, ka = cl->rk[a], kb = cl->rk[b];
+                            gpt.push_back(gi(p0, cl->RTi.as<double>() + cl->kkoff[a], pp, e, ka, ka, m, ka, m));
+                            gpt.push_back(gi(p0 + ka, cl->RTi.as<double>() + cl->kkoff[b], pp + ka, e, kb, kb, m, kb, m));
+                        }
+                        gG1.push_back(gi(ut, ut, rt, k, k, m, m, m, k));
+                        gG2.push_back(gi(pp, pp, g2, e, e, m, m, m, e));
+                        ch1.push_back(LUItem{rt, nullptr, k, k});
+                        ch2.push_back(LUItem{g2, nullptr, e, e});
+                        cId1.push_back(cp(nullptr, rti, k, k, k, k, COPY_IDENTITY));
+                        cId2.push_back(cp(nullptr, l2i, e, e, e, e, COPY_IDENTITY));
+                        tr1.push_back(TrsmItem{rt, rti, k, k, k, k});
+                        tr2.push_back(TrsmItem{g2, l2i, e, e, e, e});
+                        gQ1.push_back(gi(rti, ut, qt, k, m, k, k, m, m));
+                        gQ2.push_back(gi(l2i, pp, qt + (size_t)k * m, e, m, e, e, m, m));
                     }
-                    gG1.push_back(gi(ut, ut, rt, k, k, m, m, m, k));
-                    gG2.push_back(gi(pp, pp, g2, e, e, m, m, m, e));
-                    ch1.push_back(LUItem{rt, nullptr, k, k});
-                    ch2.push_back(LUItem{g2, nullptr, e, e});
-                    cId1.push_back(cp(nullptr, rti, k, k, k, k, COPY_IDENTITY));
-                    cId2.push_back(cp(nullptr, l2i, e, e, e, e, COPY_IDENTITY));
-                    tr1.push_back(TrsmItem{rt, rti, k, k, k, k});
-                    tr2.push_back(TrsmItem{g2, l2i, e, e, e, e});
-                    gQ1.push_back(gi(rti, ut, qt, k, m, k, k, m, m));
-                    gQ2.push_back(gi(l2i, pp, qt + (size_t)k * m, e, m, e, e, m, m));
                     gTmp.push_back(gi(qt, D, tmp, m, m, m, m, m, m));
                     gDh.push_back(gi(tmp, qt, dh, m, m, m, m, m, m));
                     cE.push_back(cp(dh + (size_t)k * m + k, ee, e, e, m, e, COPY_PLAIN));

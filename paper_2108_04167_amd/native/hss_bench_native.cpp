@@ -2,7 +2,11 @@
 // on seeded synthetic points.  It exists so that hardware-counter collection (rocprofv3 --pmc) can wrap
 // a plain executable; the measured kernels and launch shapes are those of the library.
 //
-//   hss_bench_native n r s leaf h maxit [nsolve]
+//   hss_bench_native n r s leaf h maxit [nsolve [key=value ...]]
+//
+// key=value pairs after nsolve are passed to hss_set_i64 before the compression (e.g. sampling=1 clustering=1
+// adaptive_start=128), so that the same driver exercises every option of the library (it is also what the host
+// sanitizer build of the library is run through).
 //
 // After the library calls it runs the library's hss_stream_copy three times on 2^27 doubles (1 GiB read,
 // 1 GiB written per launch): the reference that converts the memory counters' raw readings into bytes.
@@ -14,6 +18,8 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <string>
 #include <vector>
 
 #include "../../include/hss_svm.h"
@@ -69,6 +75,15 @@ int main(int argc, char** argv) {
     hss_ctx* ctx = nullptr;
     CHECK(hss_create(&ctx, nullptr));
     CHECK(hss_set_i64(ctx, "sample_width", s));
+    for (int a = 8; a < argc; ++a) {
+        const char* eq = strchr(argv[a], '=');
+        if (!eq) {
+            fprintf(stderr, "expected key=value, got %s\n", argv[a]);
+            return 2;
+        }
+        const std::string key(argv[a], eq - argv[a]);
+        CHECK(hss_set_i64(ctx, key.c_str(), atoll(eq + 1)));
+    }
     double t0 = now();
     CHECK(hss_compress(ctx, dF, dy, n, r, h, leaf, 1e-3));
     hipDeviceSynchronize();
@@ -83,6 +98,19 @@ int main(int argc, char** argv) {
     int64_t nm = 0;
     CHECK(admm_svm_train(ctx, 1.0, 1.0, maxit, nullptr, nullptr, nullptr, &bias, &nm));
     double t4 = now();
+    {   // the C-sweep in lockstep at another beta (re-factorization with the cached bases) and the label loop
+        const double Cs[3] = {0.1, 1.0, 10.0};
+        double b3[3];
+        int64_t m3[3];
+        double *dz = nullptr, *ddec = nullptr;
+        if (hipMalloc(&dz, sizeof(double) * n * 3) != hipSuccess || hipMalloc(&ddec, sizeof(double) * 256) != hipSuccess) return 1;
+        CHECK(admm_svm_train_multi(ctx, Cs, 3, 2.0, maxit, nullptr, dz, nullptr, b3, m3));
+        CHECK(svm_decision(ctx, dF, n < 256 ? n : 256, dz + n, b3[1], ddec));
+        double err = 0.0;
+        CHECK(hss_error_estimate(ctx, 4, 7, &err));
+        hipFree(dz);
+        hipFree(ddec);
+    }
     hss_stats_t st;
     CHECK(hss_stats(ctx, &st));
     printf("n %lld r %d s %d leaf %d: compress %.4f s (sampling kernel %.4f s, %.2f TFLOP/s), factor %.4f s, "
@@ -109,5 +137,6 @@ int main(int argc, char** argv) {
     hipFree(dF);
     hipFree(dy);
     hipFree(dx);
+    fflush(stdout);
     return 0;
 }
