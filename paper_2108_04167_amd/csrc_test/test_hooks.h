@@ -16,6 +16,9 @@ int hsx_inverse(void* stream, int nmat, const int32_t* n_host, const int64_t* of
 int hsx_chol(void* stream, int nmat, const int32_t* n_host, const int64_t* offs_host, double* base_dev);
 int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, const int64_t* moff_host, int32_t kcap,
                double rel, double abs_tol, int32_t gram, int32_t* ranks_host, int32_t* J_host, double* U_dev);
+int hsx_row_id_blocks(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, const int64_t* moff_host, int32_t kcap,
+                      double rel, double abs_tol, int32_t gram, int32_t rows_per_block, int32_t* ranks_host,
+                      int32_t* J_host, double* U_dev);
 int hsx_omega(void* stream, double* Om_dev, int64_t n, int32_t s, uint64_t seed);
 #ifdef __cplusplus
 }

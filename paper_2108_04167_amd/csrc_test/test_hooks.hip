@@ -108,6 +108,15 @@ int hsx_chol(void* stream, int nmat, const int32_t* n_host, const int64_t* offs_
 // msz_t x k_t blocks one after the other in node order; caller sizes it as rows x kcap).
 int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, const int64_t* moff_host, int32_t kcap,
                double rel, double abs_tol, int32_t gram, int32_t* ranks_host, int32_t* J_host, double* U_dev) {
+    return hsx_row_id_blocks(stream, A_dev, ld, nnodes, moff_host, kcap, rel, abs_tol, gram, 32, ranks_host, J_host, U_dev);
+}
+
+// The same with the number of rows a workgroup of the row-wise kernels takes (the library uses 32): a different
+// split of the same work over the grid must give the same bits.
+int hsx_row_id_blocks(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, const int64_t* moff_host, int32_t kcap,
+                      double rel, double abs_tol, int32_t gram, int32_t rows_per_block, int32_t* ranks_host,
+                      int32_t* J_host, double* U_dev) {
+    if (rows_per_block < 4 || rows_per_block % 4) return HSS_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = moff_host[nnodes];
     int maxm = 0;
@@ -126,7 +135,7 @@ int hsx_row_id(void* stream, const double* A_dev, int32_t ld, int32_t nnodes, co
     HIP_TRY(hipMemcpyAsync(W.p, A_dev, sizeof(double) * rows * ld, hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipMemcpyAsync(moff.p, moff_host, sizeof(int64_t) * (nnodes + 1), hipMemcpyHostToDevice, st));
     IdLevelArgs ia;
-    ia.W = W.as<double>(); ia.ld = ld; ia.moff = moff.as<int64_t>(); ia.kcap = kcap; ia.kc = kcap; ia.rows_per_block = 32;
+    ia.W = W.as<double>(); ia.ld = ld; ia.moff = moff.as<int64_t>(); ia.kcap = kcap; ia.kc = kcap; ia.rows_per_block = rows_per_block;
     ia.rel = rel; ia.abs_tol = abs_tol; ia.done = done.as<int>(); ia.r11 = r11.as<double>(); ia.jtmp = jtmp.as<int>();
     ia.rk = rk.as<int>(); ia.Lc = Lc.as<double>(); ia.sel = sel.as<int>(); ia.active = nullptr;
     if (gram) {
