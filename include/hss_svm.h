@@ -60,61 +60,65 @@ const char* hss_strerror(int code);
 int  hss_create(hss_ctx** out, void* hip_stream);
 void hss_destroy(hss_ctx* ctx);
 
-/* Options; set before hss_compress.
- *   i64: "sample_width" s   number of random columns (default 128; padded with zero columns to a multiple of 128 inside)
- *        "oversample"   p   rank cap is s - p unless "max_rank" is set (default s/2: with ranks that hit the
- *                           cap a small p over-fits the sample and the nested bases amplify the error
- *                           level by level)                                    (oversampling, end of Sec. 3.2)
- *        "max_rank"         explicit rank cap per node (default 0 = s - p)
- *        "seed"             seed of the counter-based generator that draws Omega (default 0)
-        "merge_top"        1 (default): the ULV solve replaces the levels from the root down to a cut level by one
-                           product with the inverse of the reduced matrix at the cut (chosen at factorization
-                           time so that a solve takes the least modelled time; at most 4096 rows); 0: every
-                           level is a launch of its own.  Set before hss_ulv_factor.
-        "sampling"         how the off-diagonal block rows are sampled.  0 (default): random sample S = K Omega
-                           (randomized sampling, end of Sec. 3.2).  1: neighbour-based, the paper's own compressor
-                           (Sec. 3.1, first bullet): the sample of a node's block row is K(rows, N) with N the
-                           "sample_width" closest distinct approximate nearest neighbours of the node's row points
-                           that lie outside the node -- entries of K itself, no product with a random matrix and
-                           no O(n^2) work.  Neighbours: "ann_neighbours" k <= 64 per point (default 64) from
-                           "ann_trees" trees (default 3: the cluster-tree order plus random projection trees,
-                           directions from "seed") with exact search inside cells of "ann_cell" points (default
-                           512, rounded up to leaf * 2^j).  Ignored by hss_compress_with_samples; the adaptive
-                           width does not apply.  n < 2^31.
-        "ann_neighbours", "ann_cell", "ann_trees"
-        "clustering"       rule of the cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; always a perfect
-                           binary tree with equal-size nodes).  0 (default): a node is split at the median of
-                           the coordinate of largest variance.  1: data-driven -- along the line between the two
-                           centres of a 2-means pass over the node ("clustering_iterations" Lloyd steps, default
-                           2, started from the point farthest from the node's mean and the point farthest from
-                           that one), at the median of the projections.  The rule is free of summation order
-                           (centres from exact fixed-point sums, the rest per point), n < 2^24.
-        "clustering_iterations"
-        "cache_basis"      1 (default): the parts of the ULV factorization that depend on the generators only --
-                           the orthogonal change of basis of every node, the reduced bases, the parents'
-                           off-diagonal blocks -- are kept from the first factorization of a compression and
-                           reused by later ones with other beta (Sec. 3.2: what is computed once is reused
-                           across the grid); the factors are bit-identical either way.  0: recomputed every time.
-        "graph"            1: admm_svm_train records two iterations (all launches of two ULV solves and two vector
-                           updates) into a HIP graph and replays it, on a stream of the library's own that is
-                           ordered after / before the context's stream by events; 0 (default): every launch is
-                           issued eagerly on the context's stream.  The iterates are the same either way; the
-                           replay measured 3 - 35 % slower per iteration than eager launches on gfx950, the host
-                           never being the bottleneck of an iteration.
-        "adaptive_start"   s0 > 0: adaptive sample width (oversampling / truncation of every block to the
-                           tolerance, end of Sec. 3.2).  The decompositions of a tree level first see the leading
-                           s0 columns of the sample; while a node of the level is cut by the sample's rank cap
-                           (w - p at width w, p = "oversample", default w/2) rather than by the tolerance, and
-                           columns are left, "adaptive_step" more columns of Omega are sampled (for all rows,
-                           and carried up through the finished levels) and the cut nodes -- only those -- are
-                           decomposed again.  "sample_width" (or the width of a caller's Omega) is then the
-                           LARGEST width, and the final rank cap is min("max_rank", s - p(s)).  s0, the step and
-                           s must be multiples of 128.  Default 0: off, all s columns are sampled at once.
-        "adaptive_step"    columns added per widening (default 128)
- *        "psd_guard"        1 (default): after compression estimate lambda_min(K~) and, if negative,
- *                           add delta = 1.1*|lambda_min| to the diagonal so that the approximate
- *                           problem (eq. 8) stays convex, as Algorithm 3 presupposes; 0: off
- *   f64: "abs_tol"          absolute pivot threshold of the interpolative decompositions (default 1e-8) */
+/* Options (hss_set_i64 unless marked f64); set before hss_compress unless stated otherwise.
+ *
+ * Sampling and truncation (end of Sec. 3.2: randomized sampling with oversampling, every block truncated to the
+ * tolerance; Sec. 3.1 first bullet: neighbour-based sampling)
+ *   "sample_width" s     number of sample columns (default 128; padded with zero columns to a multiple of 128 inside)
+ *   "oversample"   p     rank cap is s - p unless "max_rank" is set (default s/2: with ranks that hit the cap a small
+ *                        p over-fits the sample and the nested bases amplify the error level by level)
+ *   "max_rank"           explicit rank cap per node (default 0 = s - p)
+ *   "seed"               seed of the counter-based generator (Omega, random projection directions; default 0)
+ *   "abs_tol" (f64)      absolute pivot threshold of the interpolative decompositions (default 1e-8)
+ *   "adaptive_start" s0  > 0: adaptive sample width.  The decompositions of a tree level first see the leading s0
+ *                        columns of the sample; while a node of the level is cut by the sample's rank cap (w - p at
+ *                        width w, p = "oversample", default w/2) rather than by the tolerance, and columns are left,
+ *                        "adaptive_step" more columns of Omega are sampled (for all rows, and carried up through the
+ *                        finished levels) and the cut nodes -- only those -- are decomposed again.  "sample_width"
+ *                        (or the width of a caller's Omega) is then the LARGEST width, and the final rank cap is
+ *                        min("max_rank", s - p(s)).  s0, the step and s must be multiples of 128.  Default 0: off, all
+ *                        s columns are sampled at once.
+ *   "adaptive_step"      columns added per widening (default 128)
+ *   "sampling"           0 (default): random sample S = K Omega.  1: neighbour-based, the paper's own compressor: the
+ *                        sample of a node's block row is K(rows, N) with N the "sample_width" closest distinct
+ *                        approximate nearest neighbours of the node's row points that lie outside the node -- entries
+ *                        of K itself, no product with a random matrix and no O(n^2) work.  Ignored by
+ *                        hss_compress_with_samples; the adaptive width does not apply; n < 2^31.
+ *   "ann_neighbours" k   neighbours per point, 1 .. 64 (default 64)
+ *   "ann_trees"          search trees (default 3): tree 0 = the cells of the cluster-tree order, the others random
+ *                        projection trees (directions uniform in (-1,1)^r from Philox4x32-10 keyed by "seed"); with a
+ *                        single tree no search leaves a cell and nodes above the cell size get no column at all
+ *   "ann_cell"           points per cell, searched exhaustively (default 512, rounded up to leaf * 2^j)
+ *
+ * Cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; always a perfect binary tree with equal-size nodes)
+ *   "clustering"         0 (default): a node is split at the median of the coordinate of largest variance.
+ *                        1: data-driven -- along the line between the two centres of a 2-means pass over the node
+ *                        (started from the point farthest from the node's mean and the point farthest from that
+ *                        one), at the median of the projections.  The rule is free of summation order (centres from
+ *                        exact fixed-point sums, the rest per point); n < 2^24.
+ *   "clustering_iterations"  Lloyd steps of that pass, 0 .. 64 (default 2)
+ *
+ * Definiteness
+ *   "psd_guard"          1 (default): after compression estimate lambda_min(K~) and, if negative, add
+ *                        delta = 1.1*|lambda_min| to the diagonal so that the approximate problem (eq. 8) stays
+ *                        convex, as Algorithm 3 presupposes; 0: off
+ *
+ * Factorization, solve, iteration (may be set any time before the call they affect)
+ *   "merge_top"          1 (default): the ULV solve replaces the levels from the root down to a cut level by one
+ *                        product with the inverse of the reduced matrix at the cut (chosen at factorization time so
+ *                        that a solve takes the least modelled time; at most 4096 rows); 0: every level is a launch
+ *                        of its own.  Takes effect at the next hss_ulv_factor.
+ *   "cache_basis"        1 (default): the parts of the ULV factorization that depend on the generators only -- the
+ *                        orthogonal change of basis of every node, the reduced bases, the parents' off-diagonal
+ *                        blocks -- are kept from the first factorization of a compression and reused by later ones
+ *                        with another beta (Sec. 3.2: what is computed once is reused across the grid); the factors
+ *                        are bit-identical either way.  0: recomputed every time.
+ *   "graph"              1: admm_svm_train records two iterations (all launches of two ULV solves and two vector
+ *                        updates) into a HIP graph and replays it, on a stream of the library's own that is ordered
+ *                        after / before the context's stream by events; 0 (default): every launch is issued eagerly
+ *                        on the context's stream.  The iterates are the same either way; the replay measured 3 - 35 %
+ *                        slower per iteration than eager launches on gfx950.
+ * Unknown keys and values out of range return HSS_EINVAL. */
 int hss_set_i64(hss_ctx* ctx, const char* key, int64_t v);
 int hss_set_f64(hss_ctx* ctx, const char* key, double v);
 
@@ -137,9 +141,9 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
 int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h,
                               const double* Omega_dev, int32_t s, double* S_out_dev);
 
-/* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection on the
- * coordinate of largest variance), random sampling S = K Omega, interpolative decompositions level by
- * level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,
+/* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection; option "clustering"),
+ * sampling of the off-diagonal block rows (S = K Omega, or the neighbour-based sample; option "sampling"),
+ * interpolative decompositions level by level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,
  * 1 <= r <= 96, h > 0, 0 < tol < 1.  Pivots of each decomposition are kept while
  * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 and s <= 2048 (s <= 1024 for
  * tol < 3e-5), EUNSUPPORTED beyond.
