@@ -112,7 +112,7 @@ def cells_of_projection_tree(F, cell, direction):
             for f in range(r):
                 p = p + F[idx, f] * d[f]
             order = np.lexsort((idx, p))
-            half = idx.size // 2
+            half = (idx.size + 1) // 2           # same shape as the cluster tree: ceil(p/2) points go left
             nxt.append(idx[order[:half]])
             nxt.append(idx[order[half:]])
         level = nxt
@@ -132,17 +132,20 @@ def knn_in_cells(F, cells, k):
     return idx, dist
 
 
-def ann_projection_trees(F, k, cell, trees, seed=0, directions=None):
+def ann_projection_trees(F, k, cell, trees, seed=0, directions=None, first_cells=None):
     """Approximate k nearest neighbours: tree 0 = contiguous runs of `cell` points in the
-    given order (for points in cluster-tree order: the cells of that tree), trees
-    1 .. trees-1 = random projection trees; exact search inside every cell; lists merged.
-    directions(tree, level, node) -> (r,) supplies the random directions (default: normal
-    numbers from a generator seeded with `seed`)."""
+    given order (for points in cluster-tree order: the cells of that tree; `first_cells`
+    = offsets of the runs when they are not all `cell` long, then `cell` is the longest),
+    trees 1 .. trees-1 = random projection trees; exact search inside every cell; lists
+    merged.  directions(tree, level, node) -> (r,) supplies the random directions
+    (default: normal numbers from a generator seeded with `seed`)."""
     n = F.shape[0]
     if directions is None:
         rng = np.random.default_rng(seed)
         directions = lambda t, l, node: rng.standard_normal(F.shape[1])
-    cells = [np.arange(i, min(n, i + cell), dtype=np.int64) for i in range(0, n, cell)]
+    if first_cells is None:
+        first_cells = list(range(0, n, cell)) + [n]
+    cells = [np.arange(a, b, dtype=np.int64) for a, b in zip(first_cells[:-1], first_cells[1:])]
     idx, dist = knn_in_cells(F, cells, k)
     for t in range(1, trees):
         tree_cells = cells_of_projection_tree(F, cell, lambda l, node: directions(t, l, node))
@@ -181,10 +184,8 @@ def compress_ann(Fp, h, leaf, nbr_idx, nbr_dist, s, rel_tol, abs_tol=0.0, kmax=N
     fl = H.first_leaf()
     info = {"columns": {}}
     for l in range(H.L, -1, -1):
-        width = n >> l
         for t in H.level_nodes(l):
-            i = t - ((1 << l) - 1)
-            lo, hi = i * width, (i + 1) * width
+            lo, hi = H.span(t)
             if H.is_leaf(t):
                 rows = np.arange(lo, hi)
                 H.D[t - fl] = gaussian_kernel(Fp[rows], Fp[rows], h)

@@ -20,7 +20,9 @@ Represented matrix: diagonal leaf blocks D_t exactly; K~(I_a, I_b) = Uh_a B_ab U
 with Uh_leaf = U_leaf and Uh_t = blkdiag(Uh_a, Uh_b) U_t.
 
 Nodes are numbered in heap order: root 0, children of t are 2t+1 and 2t+2; the
-leaves are the last 2^L nodes, left to right.
+leaves are the last 2^L nodes, left to right.  Any n: the tree has the shape
+`oracle.tree` defines (all leaves on level L, sizes ceil/floor of n / 2^L, leaf i
+holds the rows loff[i] .. loff[i+1]-1 of the cluster-tree order).
 
 Which rows an ID picks (and so the ranks) is not unique: "parity unpinned".
 What is pinned (tests/test_oracle_hss_ulv.py): reconstruction error <= tolerance
@@ -34,6 +36,7 @@ import numpy as np
 import scipy.linalg as sla
 
 from .kernel import gaussian_kernel
+from .tree import tree_depth, leaf_offsets
 
 
 def sample(Fp, Omega, h, block=512):
@@ -78,11 +81,10 @@ class HSS:
 
     def __init__(self, n, leaf):
         self.n = int(n)
-        self.leaf = int(leaf)
-        nl = self.n // self.leaf
-        if nl * self.leaf != self.n or nl & (nl - 1) or nl < 1:
-            raise ValueError("n must be leaf * 2^L")
-        self.L = nl.bit_length() - 1
+        self.leaf = int(leaf)                   # largest leaf size
+        self.L = tree_depth(self.n, self.leaf)
+        nl = 1 << self.L
+        self.loff = leaf_offsets(self.n, self.L)   # rows of leaf i: loff[i] .. loff[i+1]-1
         self.nnodes = 2 * nl - 1
         self.D = [None] * nl                    # leaf diagonal blocks, left to right
         self.U = [None] * self.nnodes           # (size_t, k_t); None at the root
@@ -102,9 +104,21 @@ class HSS:
     def rank(self, t):
         return 0 if self.U[t] is None else self.U[t].shape[1]
 
+    def leaf_rows(self, i):
+        """Rows (cluster-tree order) of leaf i, counted from the left."""
+        return np.arange(self.loff[i], self.loff[i + 1])
+
+    def span(self, t):
+        """First row and one past the last row of the points under node t."""
+        l = (t + 1).bit_length() - 1
+        i = t - ((1 << l) - 1)
+        w = 1 << (self.L - l)                   # leaves under a node of level l
+        return int(self.loff[i * w]), int(self.loff[(i + 1) * w])
+
     def size(self, t):
         if self.is_leaf(t):
-            return self.leaf
+            i = t - self.first_leaf()
+            return int(self.loff[i + 1] - self.loff[i])
         return self.rank(2 * t + 1) + self.rank(2 * t + 2)
 
     def ranks(self):
@@ -132,7 +146,7 @@ def compress(Fp, h, leaf, Omega, rel_tol, abs_tol=0.0, kmax=None, S=None):
         for t in H.level_nodes(l):
             if H.is_leaf(t):
                 i = t - fl
-                rows = np.arange(i * leaf, (i + 1) * leaf)
+                rows = H.leaf_rows(i)
                 Dt = gaussian_kernel(Fp[rows], Fp[rows], h)
                 H.D[i] = Dt
                 St = S[rows] - Dt @ Omega[rows]
@@ -196,7 +210,7 @@ def compress_adaptive(Fp, h, leaf, Omega, rel_tol, abs_tol=0.0, s0=None, step=12
         for t in H.level_nodes(l):
             if H.is_leaf(t):
                 i = t - fl
-                rows = np.arange(i * leaf, (i + 1) * leaf)
+                rows = H.leaf_rows(i)
                 H.D[i] = gaussian_kernel(Fp[rows], Fp[rows], h)
                 St[t] = S[rows] - H.D[i] @ Omega[rows]
                 Ot[t] = Omega[rows]
@@ -250,18 +264,13 @@ def nested_basis(H, t):
 
 def densify(H):
     """The n x n matrix the generators represent (small n only)."""
-    n, m = H.n, H.leaf
+    n = H.n
     A = np.zeros((n, n))
     fl = H.first_leaf()
-    for i in range(n // m):
-        A[i * m:(i + 1) * m, i * m:(i + 1) * m] = H.D[i]
-
-    def span(t):
-        l = (t + 1).bit_length() - 1
-        i = t - ((1 << l) - 1)
-        w = n >> l
-        return i * w, (i + 1) * w
-
+    for i in range(len(H.D)):
+        a0, a1 = H.loff[i], H.loff[i + 1]
+        A[a0:a1, a0:a1] = H.D[i]
+    span = H.span
     for t in range(fl):
         a, b = 2 * t + 1, 2 * t + 2
         Ua, Ub = nested_basis(H, a), nested_basis(H, b)
@@ -277,13 +286,13 @@ def matvec(H, x):
     """y = K~ x for x in cluster-tree order: up-sweep x~ = U^T(.), down-sweep
     through B, leaves add D x (the standard two-pass HSS product)."""
     x = np.asarray(x, dtype=np.float64)
-    m = H.leaf
+    lo = H.loff
     fl = H.first_leaf()
     xt = [None] * H.nnodes
     for t in range(H.nnodes - 1, 0, -1):
         if H.is_leaf(t):
             i = t - fl
-            xt[t] = H.U[t].T @ x[i * m:(i + 1) * m]
+            xt[t] = H.U[t].T @ x[lo[i]:lo[i + 1]]
         else:
             xt[t] = H.U[t].T @ np.concatenate([xt[2 * t + 1], xt[2 * t + 2]])
     g = [None] * H.nnodes
@@ -291,9 +300,9 @@ def matvec(H, x):
     for t in range(H.nnodes):
         if H.is_leaf(t):
             i = t - fl
-            y[i * m:(i + 1) * m] = H.D[i] @ x[i * m:(i + 1) * m]
+            y[lo[i]:lo[i + 1]] = H.D[i] @ x[lo[i]:lo[i + 1]]
             if t != 0:
-                y[i * m:(i + 1) * m] += H.U[t] @ g[t]
+                y[lo[i]:lo[i + 1]] += H.U[t] @ g[t]
             continue
         a, b = 2 * t + 1, 2 * t + 2
         ka = H.rank(a)
@@ -331,5 +340,5 @@ def add_diagonal(H, delta):
     """K~ <- K~ + delta*I (in place, leaf diagonal blocks only)."""
     if delta != 0.0:
         for i in range(len(H.D)):
-            H.D[i] = H.D[i] + delta * np.eye(H.leaf)
+            H.D[i] = H.D[i] + delta * np.eye(H.D[i].shape[0])
     return H

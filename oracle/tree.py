@@ -2,6 +2,13 @@
 (`cluster_tree`) or along the line between the two centres of a 2-means pass over the
 node (`cluster_tree_2means`, data-driven).
 
+Shape of the tree for any number of points n and largest leaf size `leaf`
+(`tree_depth`, `leaf_offsets`): the depth L is the smallest one with
+ceil(n / 2^L) <= leaf; a node of p points gives its lower ceil(p/2) points (in the
+node's sort order) to the left child and the other floor(p/2) to the right one, on
+every level down to L.  All leaves are on level L and their sizes differ by at most
+one; with n = leaf * 2^L every leaf holds exactly `leaf` points.
+
 The paper only says that the points are clustered/reordered before compression
 so that off-diagonal blocks become low-rank (Sec. 1.2, first bullet; Fig. 1).
 The reading used here: a perfect binary tree; a node's points are split at the
@@ -15,24 +22,45 @@ import numpy as np
 TIE = 1e-9   # relative width of a tie between variances
 
 
+def tree_depth(n, leaf):
+    """Smallest L with ceil(n / 2^L) <= leaf."""
+    n, leaf = int(n), int(leaf)
+    if n < 1 or leaf < 1:
+        raise ValueError("n and leaf must be positive")
+    L = 0
+    while -(-n // (1 << L)) > leaf:
+        L += 1
+    return L
+
+
+def leaf_offsets(n, L):
+    """Offsets (length 2^L + 1) of the leaves in leaf order: ceil(p/2) of a node's p
+    points go left, floor(p/2) right, L times."""
+    off = [0, int(n)]
+    for _ in range(L):
+        nxt = [0]
+        for a, b in zip(off[:-1], off[1:]):
+            mid = a + (b - a + 1) // 2
+            nxt += [mid, b]
+        off = nxt
+    return np.asarray(off, dtype=np.int64)
+
+
 def cluster_tree(F, leaf):
     """Return perm (int64, length n): the points in leaf order, left to right.
 
     Node rule: c = lowest coordinate whose population variance over the node
     is at least (1 - 1e-9) times the largest one; sort the node's points by
-    (value of coordinate c, original index); lower half -> left child, upper
-    half -> right child; stop when the node holds `leaf` points.
-    n must equal leaf * 2^L.
+    (value of coordinate c, original index); lower ceil(p/2) points -> left child,
+    the rest -> right child; stop on level `tree_depth(n, leaf)`.
     """
     F = np.asarray(F, dtype=np.float64)
     n = F.shape[0]
-    nl = n // leaf
-    if nl * leaf != n or nl & (nl - 1):
-        raise ValueError("n must be leaf * 2^L")
+    L = tree_depth(n, leaf)
     out = []
 
-    def split(idx):
-        if idx.size == leaf:
+    def split(idx, depth):
+        if depth == L:
             out.append(idx)
             return
         sub = F[idx]
@@ -40,11 +68,11 @@ def cluster_tree(F, leaf):
         c = int(np.flatnonzero(var >= var.max() * (1.0 - TIE))[0])
         order = np.lexsort((idx, sub[:, c]))     # primary key value, secondary original index
         idx = idx[order]
-        half = idx.size // 2
-        split(idx[:half])
-        split(idx[half:])
+        half = (idx.size + 1) // 2
+        split(idx[:half], depth + 1)
+        split(idx[half:], depth + 1)
 
-    split(np.arange(n, dtype=np.int64))
+    split(np.arange(n, dtype=np.int64), 0)
     return np.concatenate(out)
 
 
@@ -64,7 +92,7 @@ def _dist2(sub, c):
 def cluster_tree_2means(F, leaf, iters=2):
     """Data-driven cluster tree (the paper's clustering preprocess, Sec. 1.1 last
     paragraph / Sec. 1.2 first bullet: the points are grouped so that off-diagonal
-    blocks of the kernel matrix get low rank).  Perfect binary tree as in
+    blocks of the kernel matrix get low rank).  Tree shape as in
     `cluster_tree`, but a node is split along the line between the two centres of a
     2-means pass over its points instead of along a coordinate axis.
 
@@ -81,13 +109,11 @@ def cluster_tree_2means(F, leaf, iters=2):
     farthest from a;  centres (ca, cb) = (a, b);  `iters` times: points with
     dist2(., ca) <= dist2(., cb) form A, the others B; stop if one is empty;
     (ca, cb) = (mean A, mean B);  then sort the node by
-    (sum_f (x_f - ca_f) (cb_f - ca_f), original index), lower half -> left child.
+    (sum_f (x_f - ca_f) (cb_f - ca_f), original index), lower ceil(p/2) -> left child.
     """
     F = np.asarray(F, dtype=np.float64)
     n, r = F.shape
-    nl = n // leaf
-    if nl * leaf != n or nl & (nl - 1):
-        raise ValueError("n must be leaf * 2^L")
+    L = tree_depth(n, leaf)
     amax = float(np.abs(F).max()) if n else 0.0
     if not np.isfinite(amax):
         raise ValueError("non-finite feature")
@@ -105,8 +131,8 @@ def cluster_tree_2means(F, leaf, iters=2):
 
     out = []
 
-    def split(idx):
-        if idx.size == leaf:
+    def split(idx, depth):
+        if depth == L:
             out.append(idx)
             return
         sub = F[idx]
@@ -123,9 +149,9 @@ def cluster_tree_2means(F, leaf, iters=2):
         for f in range(r):
             p = p + (sub[:, f] - ca[f]) * d[f]
         idx = idx[np.lexsort((idx, p))]
-        half = idx.size // 2
-        split(idx[:half])
-        split(idx[half:])
+        half = (idx.size + 1) // 2
+        split(idx[:half], depth + 1)
+        split(idx[half:], depth + 1)
 
-    split(np.arange(n, dtype=np.int64))
+    split(np.arange(n, dtype=np.int64), 0)
     return np.concatenate(out)

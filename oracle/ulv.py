@@ -44,7 +44,7 @@ def ulv_factor(H, beta):
     Ut = [None] * nn      # reduced basis passed to the parent
     for t in range(nn - 1, -1, -1):
         if H.is_leaf(t):
-            D = H.D[t - fl] + beta * np.eye(H.leaf)
+            D = H.D[t - fl] + beta * np.eye(H.D[t - fl].shape[0])
             U = H.U[t]
         else:
             a, b = 2 * t + 1, 2 * t + 2
@@ -90,12 +90,12 @@ def ulv_solve(F, b):
     Bm = b.reshape(H.n, -1)
     nn = H.nnodes
     fl = H.first_leaf()
-    m = H.leaf
+    lo = H.loff              # rows of leaf i: lo[i] .. lo[i+1]-1
     red = [None] * nn        # reduced right-hand side passed up
     ce = [None] * nn         # Dee^{-1} b_e kept for the way down
     for t in range(nn - 1, -1, -1):
         if H.is_leaf(t):
-            bt = Bm[(t - fl) * m:(t - fl + 1) * m]
+            bt = Bm[lo[t - fl]:lo[t - fl + 1]]
         else:
             bt = np.vstack([red[2 * t + 1], red[2 * t + 2]])
         if t == 0:
@@ -123,7 +123,7 @@ def ulv_solve(F, b):
                 xe = ce[t] - sla.lu_solve(F.lu_ee[t], F.Der[t] @ xin[t])
                 xt = F.Q[t] @ np.vstack([xin[t], xe])
         if H.is_leaf(t):
-            X[(t - fl) * m:(t - fl + 1) * m] = xt
+            X[lo[t - fl]:lo[t - fl + 1]] = xt
         else:
             ka = F.k[2 * t + 1]
             xin[2 * t + 1] = xt[:ka]

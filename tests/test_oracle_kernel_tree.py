@@ -88,9 +88,9 @@ def test_tree_variances_equal_up_to_rounding_count_as_tied():
 
 def test_tree_rejects_bad_sizes():
     with pytest.raises(ValueError):
-        cluster_tree(np.zeros((100, 2)), 32)
+        cluster_tree(np.zeros((0, 2)), 32)
     with pytest.raises(ValueError):
-        cluster_tree(np.zeros((96, 2)), 32)
+        cluster_tree(np.zeros((96, 2)), 0)
 
 
 # ---- data-driven cluster tree (2-means bisection) ----
