@@ -43,7 +43,7 @@ typedef struct hss_ctx hss_ctx;
 
 /* errors */
 #define HSS_OK            0
-#define HSS_EINVAL       (-1)  /* bad argument: n, r, leaf, tol, h, beta, C out of range; n != leaf*2^L; null pointer */
+#define HSS_EINVAL       (-1)  /* bad argument: n, r, leaf, tol, h, beta, C out of range; null pointer              */
 #define HSS_ESTATE       (-2)  /* call out of order: solve before factor, factor before compress, ...            */
 #define HSS_ENOMEM       (-3)  /* device or host allocation failed                                                */
 #define HSS_EHIP         (-4)  /* a HIP runtime call failed                                                       */
@@ -88,9 +88,10 @@ void hss_destroy(hss_ctx* ctx);
  *   "ann_trees"          search trees (default 3): tree 0 = the cells of the cluster-tree order, the others random
  *                        projection trees (directions uniform in (-1,1)^r from Philox4x32-10 keyed by "seed"); with a
  *                        single tree no search leaves a cell and nodes above the cell size get no column at all
- *   "ann_cell"           points per cell, searched exhaustively (default 512, rounded up to leaf * 2^j)
+ *   "ann_cell"           points per cell, searched exhaustively (default 512): the cells are the nodes of the deepest
+ *                        tree level whose nodes all hold at least that many points (the root if none does)
  *
- * Cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; always a perfect binary tree with equal-size nodes)
+ * Cluster tree (the clustering preprocess of Sec. 1.1 / 1.2; shape: see hss_compress)
  *   "clustering"         0 (default): a node is split at the median of the coordinate of largest variance.
  *                        1: data-driven -- along the line between the two centres of a 2-means pass over the node
  *                        (started from the point farthest from the node's mean and the point farthest from that
@@ -143,8 +144,11 @@ int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int3
 
 /* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection; option "clustering"),
  * sampling of the off-diagonal block rows (S = K Omega, or the neighbour-based sample; option "sampling"),
- * interpolative decompositions level by level.  F (dev, n x r), y (dev, n).  n = leaf * 2^L, leaf a multiple of 16 with 16 <= leaf <= 1024,
- * 1 <= r <= 96, h > 0, 0 < tol < 1.  Pivots of each decomposition are kept while
+ * interpolative decompositions level by level.  F (dev, n x r), y (dev, n).  Any n >= 1; `leaf` = the largest leaf
+ * size, a multiple of 16 with 16 <= leaf <= 1024; 1 <= r <= 96, h > 0, 0 < tol < 1.
+ * Shape of the tree: depth L = the smallest one with ceil(n / 2^L) <= leaf; a node of p points gives the lower
+ * ceil(p/2) of them (in the order of its split) to the left child and the rest to the right one.  All leaves are on
+ * level L and hold floor or ceil of n / 2^L points (n = leaf * 2^L: exactly `leaf` each).  Pivots of each decomposition are kept while
  * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 and s <= 2048 (s <= 1024 for
  * tol < 3e-5), EUNSUPPORTED beyond.
  * Drops any previous compression and factorization held by the context.
@@ -231,7 +235,8 @@ int hss_stats(hss_ctx* ctx, hss_stats_t* out_host);
  *   perm   int64[n]           perm[i] = original index of the i-th point in cluster-tree order
  *   sizes  int32[nnodes]      node size m_t (leaf size at leaves, k_a + k_b above)
  *   ranks  int32[nnodes]      k_t (0 at the root)
- *   D      double[nleaf*leaf*leaf]  leaf diagonal blocks, row-major, WITHOUT the guard's shift
+ *   D      double[sum m_t^2 over the leaves, at most n*leaf]  leaf diagonal blocks (m_t x m_t row-major, one after
+ *                             the other, left to right), WITHOUT the guard's shift
  *   U      double[sum m_t k_t]      row-major (m_t x k_t) per non-root node, heap order
  *   J      int32[sum k_t]           skeleton rows of each node (local row indices), heap order
  *   B      double[sum k_a k_b]      row-major (k_a x k_b) per inner node t with children a, b, heap order
@@ -254,8 +259,8 @@ int hss_export_neighbours(hss_ctx* ctx, int32_t* k_out, int32_t* idx_out, double
  * guard does not run: the represented matrix is the HSS matrix of (D, U, B) plus delta I with the caller's
  * delta >= 0 (Sec. 3.2: the compressed matrix depends on (F, h) only, so it can be computed once and kept).
  * The arrays are copied; the caller keeps ownership.  Checked on the host: perm is a permutation of 0..n-1;
- * sizes/ranks describe a perfect binary tree with leaf blocks of `leaf` rows, inner size = sum of the children's
- * ranks, 1 <= rank <= size below the root and rank 0 at the root; every J lists distinct rows of its node and
+ * sizes/ranks describe the tree of hss_compress for this n and `leaf` (leaf sizes as stated there), inner size = sum
+ * of the children's ranks, 1 <= rank <= size below the root and rank 0 at the root; every J lists distinct rows of its node and
  * U is interpolative on them (row J_j of U_t is exactly the j-th unit vector); labels are +-1.  Violations return HSS_EINVAL, ranks above 512 HSS_EUNSUPPORTED; the context is then not
  * compressed.  Returns 0 or HSS_WSHIFT (delta > 0).  Synchronous. */
 int hss_import(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,

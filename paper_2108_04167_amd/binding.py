@@ -233,9 +233,15 @@ class Context:
         p = lambda a: C.c_void_p(a.ctypes.data)
         _check(_lib.hss_export(self._h, p(perm), p(sizes), p(ranks), p(D), p(U), p(J), p(B), C.byref(delta)),
                "hss_export")
+        # leaf blocks: compact, one after the other; a (leaves, m, m) array when all leaves have one size, else a list
+        msz = sizes[(nn.value + 1) // 2 - 1:].astype(np.int64)
+        if (msz == msz[0]).all():
+            Dl = D[:msz.size * int(msz[0]) ** 2].reshape(msz.size, int(msz[0]), int(msz[0]))
+        else:
+            off = np.concatenate([[0], np.cumsum(msz * msz)])
+            Dl = [D[off[i]:off[i + 1]].reshape(int(msz[i]), int(msz[i])) for i in range(msz.size)]
         return {"n": n, "leaf": leaf, "perm": perm, "sizes": sizes, "ranks": ranks,
-                "D": D.reshape(n // leaf, leaf, leaf), "U": U[:ul.value], "J": J[:jl.value], "B": B[:bl.value],
-                "delta": delta.value}
+                "D": Dl, "U": U[:ul.value], "J": J[:jl.value], "B": B[:bl.value], "delta": delta.value}
 
     def hss_export_neighbours(self):
         """(idx, dist) of the last neighbour-based compression: (n, k) int32 / float64, cluster-tree order."""
@@ -254,7 +260,8 @@ class Context:
         n, r = F.shape
         keep = [np.ascontiguousarray(gen["perm"], dtype=np.int64), np.ascontiguousarray(gen["sizes"], dtype=np.int32),
                 np.ascontiguousarray(gen["ranks"], dtype=np.int32),
-                np.ascontiguousarray(gen["D"], dtype=np.float64).reshape(-1),
+                (np.concatenate([np.asarray(d, dtype=np.float64).reshape(-1) for d in gen["D"]])
+                 if isinstance(gen["D"], (list, tuple)) else np.ascontiguousarray(gen["D"], dtype=np.float64).reshape(-1)),
                 np.ascontiguousarray(gen["U"], dtype=np.float64), np.ascontiguousarray(gen["J"], dtype=np.int32),
                 np.ascontiguousarray(gen["B"], dtype=np.float64)]
         keep = [a if a.size else np.zeros(1, dtype=a.dtype) for a in keep]

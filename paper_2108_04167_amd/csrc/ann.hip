@@ -3,9 +3,10 @@
 // of a random sample K Omega).
 //
 // 1. Approximate nearest neighbours of every point (points in cluster-tree order):
-//      tree 0 = the cells of the cluster-tree order itself (contiguous runs of `cell` points),
-//      trees 1 .. T-1 = random projection trees (a set is split at the median of the projections on a random
-//      direction until it holds `cell` points; one merge sort of (node, projection, point) keys per level);
+//      tree 0 = the cells of the cluster-tree order itself (the nodes of one level of the cluster tree),
+//      trees 1 .. T-1 = random projection trees of the same shape (a set is split at the median of the projections
+//      on a random direction, the lower ceil(p/2) of its p points to the left, down to the cell level; one merge
+//      sort of (node, projection, point) keys per level);
 //      inside every cell an exact search: one wavefront per point keeps the point's list (k <= 64 entries, one per
 //      lane, ascending by (distance, index)), computes the distances to 64 candidates at a time (features read
 //      coalesced from a transposed copy), drops the point itself and entries already listed, sorts the 64 by a
@@ -87,11 +88,12 @@ __global__ __launch_bounds__(256) void transpose_gather_kernel(const double* __r
 
 // key of position i: (node, sum_f x_f dir[node][f], point)
 __global__ __launch_bounds__(256) void proj_keys_kernel(const double* __restrict__ Fp, int r_pad, int r,
-                                                        const int64_t* __restrict__ order, int64_t n, int64_t w,
+                                                        const int64_t* __restrict__ order, int64_t n,
+                                                        const int64_t* __restrict__ noff, int64_t nodes,
                                                         const double* __restrict__ dirs, PKey* __restrict__ keys) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     const int64_t o = order[i];
     const double* x = Fp + o * r_pad;
     const double* d = dirs + node * r;
@@ -113,7 +115,8 @@ __device__ __forceinline__ bool key_less(double da, int ia, double db, int ib) {
 
 // Exact search inside the cells of one tree, merged into the lists (see the file header).
 __global__ __launch_bounds__(256) void knn_cell_kernel(const double* __restrict__ Ft, int r, int64_t n,
-                                                       const int64_t* __restrict__ order, int cell, int k,
+                                                       const int64_t* __restrict__ order,
+                                                       const int64_t* __restrict__ celloff, int64_t ncells, int k,
                                                        int32_t* __restrict__ nbr_idx, double* __restrict__ nbr_dist) {
     __shared__ double xs[4][128];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -126,8 +129,8 @@ __global__ __launch_bounds__(256) void knn_cell_kernel(const double* __restrict_
     double ld = lane < k ? nbr_dist[pid * k + lane] : ANN_INF;
     int li = lane < k ? nbr_idx[pid * k + lane] : -1;
     if (li < 0) { ld = ANN_INF; li = 0x7fffffff; }
-    const int64_t c0 = pos / cell * cell;
-    const int64_t c1 = c0 + cell < n ? c0 + cell : n;
+    const int64_t mycell = segment_of(celloff, ncells, pos);
+    const int64_t c0 = celloff[mycell], c1 = celloff[mycell + 1];
     for (int64_t base = c0; base < c1; base += 64) {
         const int64_t cp = base + lane;
         bool valid = cp < c1 && cp != pos;
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(256) void knn_cell_kernel(const double* __restrict_
 
 // Candidate entries of a level: entry (q, j) = neighbour j of the point behind row q of the level
 __global__ __launch_bounds__(256) void cand_fill_kernel(const int64_t* __restrict__ rowpoint, const int32_t* __restrict__ rownode,
-                                                        int64_t rows, int k, int64_t width,
+                                                        int64_t rows, int k, const int64_t* __restrict__ span,
                                                         const int32_t* __restrict__ nbr_idx, const double* __restrict__ nbr_dist,
                                                         CKey* __restrict__ keys) {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -210,9 +213,9 @@ __global__ __launch_bounds__(256) void cand_fill_kernel(const int64_t* __restric
     const int64_t pid = rowpoint ? rowpoint[q] : q;
     const int node = rownode[q];
     const int cand = nbr_idx[pid * k + j];
-    const int64_t lo = (int64_t)node * width;
+    const int64_t lo = span[node], hi = span[node + 1];     // the points under the node
     CKey key{ANN_INF, 0x7fffffff, 0x7fffffff};
-    if (cand >= 0 && (cand < lo || cand >= lo + width)) key = CKey{nbr_dist[pid * k + j], node, cand};
+    if (cand >= 0 && (cand < lo || cand >= hi)) key = CKey{nbr_dist[pid * k + j], node, cand};
     keys[e] = key;
 }
 // after the sort by (node, candidate, distance): every repeat of a (node, candidate) pair is dropped
@@ -279,10 +282,22 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
     const int64_t n = c->n;
     const int r = c->r, r_pad = c->r_pad;
     if (k < 1 || k > 64 || trees < 1 || cell < 2 || n >= (int64_t(1) << 31)) return HSS_EINVAL;
-    // cells: the smallest leaf * 2^j that reaches `cell`, at most n (so that every tree has equal-size cells)
-    int64_t ce = c->leaf;
-    while (ce < cell && ce < n) ce *= 2;
-    if (ce > n) ce = n;
+    // cells: the nodes of the deepest level of the cluster tree whose nodes all hold at least `cell` points (the
+    // root if none does); every projection tree is split down to the same level
+    int lc = c->L;
+    while (lc > 0 && (n >> lc) < cell) --lc;
+    const int64_t ncells = int64_t(1) << lc;
+    // offsets of the nodes of levels 0 .. lc, level after level (level l at start[l])
+    std::vector<int64_t> offs;
+    std::vector<size_t> start(lc + 1);
+    for (int l = 0; l <= lc; ++l) {
+        const std::vector<int64_t> o = level_offsets(n, l);
+        start[l] = offs.size();
+        offs.insert(offs.end(), o.begin(), o.end());
+    }
+    DevBuf offd;
+    HSS_TRY(offd.reserve(sizeof(int64_t) * offs.size()));
+    HIP_TRY(hipMemcpyAsync(offd.p, offs.data(), sizeof(int64_t) * offs.size(), hipMemcpyHostToDevice, st));
     HSS_TRY(c->nbr_idx.reserve(sizeof(int32_t) * (size_t)n * k));
     HSS_TRY(c->nbr_dist.reserve(sizeof(double) * (size_t)n * k));
     c->ann_k = k;
@@ -295,28 +310,28 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
                        c->nbr_dist.as<double>(), cnt);
     HIP_TRY(hipGetLastError());
     size_t tmp_bytes = 0;
-    if (trees > 1 && ce < n) {
+    if (trees > 1 && lc > 0) {
         HSS_TRY(keys_a.reserve(sizeof(PKey) * (size_t)n));
         HSS_TRY(keys_b.reserve(sizeof(PKey) * (size_t)n));
         HIP_TRY(rocprim::merge_sort(nullptr, tmp_bytes, keys_a.as<PKey>(), keys_b.as<PKey>(), (size_t)n, PKeyLess(), st));
         HSS_TRY(tmp.reserve(std::max<size_t>(tmp_bytes, 16)));
-        HSS_TRY(dirs.reserve(sizeof(double) * (size_t)(n / ce) * r));
+        HSS_TRY(dirs.reserve(sizeof(double) * (size_t)ncells * r));
     }
     std::vector<double> dh;
     for (int t = 0; t < trees; ++t) {
         hipLaunchKernelGGL(iota_kernel, dim3(nb), dim3(256), 0, st, order.as<int64_t>(), n);
         HIP_TRY(hipGetLastError());
         if (t > 0) {
-            if (ce >= n) break;                       // one cell holds everything: further trees add nothing
-            int level = 0;
-            for (int64_t w = n; w > ce; w /= 2, ++level) {
-                const int64_t nodes = n / w;
+            if (lc == 0) break;                       // one cell holds everything: further trees add nothing
+            for (int level = 0; level < lc; ++level) {
+                const int64_t nodes = int64_t(1) << level;
                 dh.resize((size_t)nodes * r);
                 for (int64_t node = 0; node < nodes; ++node)
                     for (int f = 0; f < r; ++f) dh[(size_t)node * r + f] = ann_direction_component(seed, t, level, node, f);
                 HIP_TRY(hipMemcpyAsync(dirs.p, dh.data(), sizeof(double) * dh.size(), hipMemcpyHostToDevice, st));
                 hipLaunchKernelGGL(proj_keys_kernel, dim3(nb), dim3(256), 0, st, c->Fp.as<double>(), r_pad, r,
-                                   order.as<int64_t>(), n, w, dirs.as<double>(), keys_a.as<PKey>());
+                                   order.as<int64_t>(), n, offd.as<int64_t>() + start[level], nodes, dirs.as<double>(),
+                                   keys_a.as<PKey>());
                 HIP_TRY(hipGetLastError());
                 HIP_TRY(rocprim::merge_sort(tmp.p, tmp_bytes, keys_a.as<PKey>(), keys_b.as<PKey>(), (size_t)n, PKeyLess(), st));
                 hipLaunchKernelGGL(proj_unpack_kernel, dim3(nb), dim3(256), 0, st, keys_b.as<PKey>(), n, order.as<int64_t>());
@@ -328,18 +343,19 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
         hipLaunchKernelGGL(transpose_gather_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, c->Fp.as<double>(),
                            r_pad, r, order.as<int64_t>(), n, Ft.as<double>());
         hipLaunchKernelGGL(knn_cell_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, Ft.as<double>(), r, n,
-                           order.as<int64_t>(), (int)ce, k, c->nbr_idx.as<int32_t>(), c->nbr_dist.as<double>());
+                           order.as<int64_t>(), offd.as<int64_t>() + start[lc], ncells, k, c->nbr_idx.as<int32_t>(),
+                           c->nbr_dist.as<double>());
         HIP_TRY(hipGetLastError());
     }
     HIP_TRY(hipStreamSynchronize(st));                // the work buffers are released on return
     return HSS_OK;
 }
 
-// Sample columns of the N nodes of a level.  rowpoint: point behind each of the level's `rows` rows (null: row q is
-// point q, the leaf level); rownode_host: node of each row; width: points under a node.  cols_dev: N x s point
-// indices; ncols_host: how many of them each node has.
+// Sample columns of the N nodes of tree level `level`.  rowpoint: point behind each of the level's `rows` rows (null:
+// row q is point q, the leaf level); rownode_host: node of each row.  cols_dev: N x s point indices; ncols_host: how
+// many of them each node has.
 int ann_select_columns(hss_ctx* c, AnnWork& wk, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host,
-                       int64_t rows, int N, int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host) {
+                       int64_t rows, int N, int level, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host) {
     hipStream_t st = c->stream;
     const int k = c->ann_k;
     const int64_t count = rows * k;
@@ -351,14 +367,17 @@ int ann_select_columns(hss_ctx* c, AnnWork& wk, const int64_t* rowpoint, const s
     HSS_TRY(seg_lo.reserve(sizeof(int64_t) * (size_t)N));
     HSS_TRY(seg_hi.reserve(sizeof(int64_t) * (size_t)N));
     HSS_TRY(ncd.reserve(sizeof(int32_t) * (size_t)N));
+    const std::vector<int64_t> span_host = level_offsets(c->n, level);   // points under node t: span[t] .. span[t+1]-1
+    HSS_TRY(wk.span.reserve(sizeof(int64_t) * span_host.size()));
+    HIP_TRY(hipMemcpyAsync(wk.span.p, span_host.data(), sizeof(int64_t) * span_host.size(), hipMemcpyHostToDevice, st));
     size_t tb1 = 0, tb2 = 0;
     HIP_TRY(rocprim::merge_sort(nullptr, tb1, keys_a.as<CKey>(), keys_b.as<CKey>(), (size_t)count, CKeyByCand(), st));
     HIP_TRY(rocprim::merge_sort(nullptr, tb2, keys_a.as<CKey>(), keys_b.as<CKey>(), (size_t)count, CKeyByDist(), st));
     HSS_TRY(tmp.reserve(std::max<size_t>(std::max(tb1, tb2), 16)));
     HIP_TRY(hipMemcpyAsync(rn.p, rownode_host.data(), sizeof(int32_t) * (size_t)rows, hipMemcpyHostToDevice, st));
     const unsigned gb = (unsigned)((count + 255) / 256);
-    hipLaunchKernelGGL(cand_fill_kernel, dim3(gb), dim3(256), 0, st, rowpoint, rn.as<int32_t>(), rows, k, width,
-                       c->nbr_idx.as<int32_t>(), c->nbr_dist.as<double>(), keys_a.as<CKey>());
+    hipLaunchKernelGGL(cand_fill_kernel, dim3(gb), dim3(256), 0, st, rowpoint, rn.as<int32_t>(), rows, k,
+                       wk.span.as<int64_t>(), c->nbr_idx.as<int32_t>(), c->nbr_dist.as<double>(), keys_a.as<CKey>());
     HIP_TRY(hipGetLastError());
     HIP_TRY(rocprim::merge_sort(tmp.p, tb1, keys_a.as<CKey>(), keys_b.as<CKey>(), (size_t)count, CKeyByCand(), st));
     hipLaunchKernelGGL(cand_unique_kernel, dim3(gb), dim3(256), 0, st, keys_b.as<CKey>(), count, keys_a.as<CKey>());

@@ -394,7 +394,7 @@ int hss_export(hss_ctx* c, int64_t* perm, int32_t* sizes, int32_t* ranks, double
     if (!c->compressed) return HSS_ESTATE;
     hipStream_t st = c->stream;
     memcpy(perm, c->perm_host.data(), sizeof(int64_t) * c->n);
-    HIP_TRY(hipMemcpyAsync(D, c->Dleaf.p, sizeof(double) * (size_t)c->n * c->leaf, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(D, c->Dleaf.p, sizeof(double) * (size_t)c->doff[c->lev[c->L].N], hipMemcpyDeviceToHost, st));
     int64_t node = 0, uo = 0, jo = 0, bo = 0;
     for (int l = 0; l <= c->L; ++l) {      // heap order = level by level, left to right
         Level& lv = c->lev[l];

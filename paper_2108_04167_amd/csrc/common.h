@@ -28,6 +28,42 @@ static inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * 
 static inline int feature_pad(int r) { return (int)round_up(r, 28); }
 
 // ---------------------------------------------------------------------------------------------
+// Shape of the cluster tree for any number of points n and largest leaf size `leaf`: depth L = the smallest one
+// with ceil(n / 2^L) <= leaf; a node of p points (a contiguous range of the tree order) gives its first ceil(p/2)
+// points to the left child and the other floor(p/2) to the right one.  All leaves are on level L, their sizes
+// differ by at most one, and n = leaf * 2^L gives leaves of exactly `leaf` points.
+static inline int tree_depth(int64_t n, int leaf) {
+    int L = 0;
+    while (((n + (int64_t(1) << L) - 1) >> L) > leaf) ++L;
+    return L;
+}
+// offsets (2^l + 1 of them) of the nodes of level l in the tree order
+static inline std::vector<int64_t> level_offsets(int64_t n, int l) {
+    std::vector<int64_t> off{0, n};
+    for (int d = 0; d < l; ++d) {
+        std::vector<int64_t> nxt;
+        nxt.reserve(2 * off.size());
+        nxt.push_back(0);
+        for (size_t t = 0; t + 1 < off.size(); ++t) {
+            nxt.push_back(off[t] + (off[t + 1] - off[t] + 1) / 2);
+            nxt.push_back(off[t + 1]);
+        }
+        off.swap(nxt);
+    }
+    return off;
+}
+// the segment t with off[t] <= i < off[t+1] (off ascending, off[0] <= i < off[nseg])
+__device__ __forceinline__ int64_t segment_of(const int64_t* __restrict__ off, int64_t nseg, int64_t i) {
+    int64_t lo = 0, hi = nseg;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (off[mid] <= i) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Device buffer with ownership.
 struct DevBuf {
     void*  p = nullptr;

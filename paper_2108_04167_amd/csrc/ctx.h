@@ -70,12 +70,15 @@ struct hss_ctx {
     bool compressed = false, factored = false;
     bool basis_cached = false;              // QT, RT, RTi, OffD of every level hold for the current compression
     int64_t n = 0, n_pad = 0;
-    int r = 0, r_pad = 0, leaf = 0, L = 0, s = 0, s_pad = 0, kcap = 0;
+    int r = 0, r_pad = 0, leaf = 0, L = 0, s = 0, s_pad = 0, kcap = 0;   // leaf: the largest leaf size (tree_depth)
     double h = 0.0, tol = 0.0, delta = 0.0, beta = -1.0;
     int warnings = 0;
     int width_used = 0;                     // sample columns the decompositions ended up using
     int64_t nodes_redone = 0;               // node decompositions repeated after widening the sample
-    DevBuf Fp, nu, yp, perm, Dleaf;
+    DevBuf Fp, nu, yp, perm;
+    DevBuf Dleaf;                           // leaf diagonal blocks D_t (m_t x m_t row-major), leaf t at doff[t]
+    std::vector<int64_t> doff;              // prefix sums of m_t^2 over the leaves            [2^L + 1]
+    bool leaves_even = false;               // every leaf size is even: 16-byte loads allowed on the D_t
     DevBuf nbr_idx, nbr_dist;               // neighbour lists (n x ann_k, cluster-tree order), neighbour-based sampling
     int ann_k = 0;
     std::vector<int64_t> perm_host;
@@ -112,10 +115,10 @@ int noalloc_scratch_for_current_device(double** out);
 // ann.hip
 int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed);
 struct AnnWork {    // work buffers of ann_select_columns, reused across the levels of one compression
-    DevBuf rn, keys_a, keys_b, tmp, seg_lo, seg_hi, ncd;
+    DevBuf rn, keys_a, keys_b, tmp, seg_lo, seg_hi, ncd, span;
 };
 int ann_select_columns(hss_ctx* c, AnnWork& wk, const int64_t* rowpoint, const std::vector<int32_t>& rownode_host,
-                       int64_t rows, int N, int64_t width, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host);
+                       int64_t rows, int N, int level, int s, int64_t* cols_dev, std::vector<int32_t>& ncols_host);
 double ann_direction_component(uint64_t seed, int tree, int level, int64_t node, int f);
 // hss.hip
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,

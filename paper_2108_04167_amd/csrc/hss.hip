@@ -130,9 +130,14 @@ int build_matvec_tables(hss_ctx* c) {
     }
     Level& leafl = c->lev[L];
     std::vector<GemvItem> dd(leafl.N);
-    for (int t = 0; t < leafl.N; ++t)
-        dd[t] = GemvItem{c->Dleaf.as<double>() + (size_t)t * c->leaf * c->leaf, mvx + (size_t)t * c->leaf,
-                         mvy + (size_t)t * c->leaf, nullptr, c->leaf, c->leaf, c->leaf, GEMV_DENSE};
+    bool leaves_even = true;
+    for (int t = 0; t < leafl.N; ++t) {
+        const int m = leafl.msz[t];
+        if (m & 1) leaves_even = false;
+        dd[t] = GemvItem{c->Dleaf.as<double>() + c->doff[t], mvx + leafl.moff[t], mvy + leafl.moff[t], nullptr, m, m, m,
+                         GEMV_DENSE};
+    }
+    c->leaves_even = leaves_even;
     HSS_TRY(upload(c, leafl.mv_leaf_d, dd));
     HIP_TRY(hipStreamSynchronize(st));   // the host vectors above go out of scope
     c->arena.reset();
@@ -160,7 +165,7 @@ int hss_matvec_perm(hss_ctx* c) {
         if (l < L) HSS_TRY(bgemv_launch(st, lv.mv_dn_u.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, lv.mv_vec, 1.0, 0.0));
     }
     Level& leafl = c->lev[L];
-    HSS_TRY(bgemv_launch(st, leafl.mv_leaf_d.as<GemvItem>(), leafl.N, c->leaf, c->leaf, true, 1.0, 0.0));
+    HSS_TRY(bgemv_launch(st, leafl.mv_leaf_d.as<GemvItem>(), leafl.N, leafl.maxm, leafl.maxm, c->leaves_even, 1.0, 0.0));
     if (L >= 1) HSS_TRY(bgemv_launch(st, leafl.mv_dn_u.as<GemvItem>(), leafl.N, leafl.maxm, leafl.maxk, leafl.mv_vec, 1.0, 1.0));
     if (c->delta != 0.0) HSS_TRY(vec_axpby(st, mvy, mvx, c->delta, 1.0, c->n));
     return HSS_OK;
@@ -238,10 +243,13 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
                       const double* Omega, int s_in) {
     if (!c || !F || !y) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol < 1.0)) return HSS_EINVAL;
-    if (leaf < 16 || leaf % 16 != 0 || n % leaf != 0) return HSS_EINVAL;
-    const int64_t nl = n / leaf;
-    if (nl & (nl - 1)) return HSS_EINVAL;
+    if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
     if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
+    const int L = tree_depth(n, leaf);                       // any n: leaves of ceil or floor of n / 2^L points
+    if (L > 24) return HSS_EUNSUPPORTED;
+    const int64_t nl = int64_t(1) << L;
+    const std::vector<int64_t> loff = level_offsets(n, L);   // rows of leaf t: loff[t] .. loff[t+1]-1
+    const int maxleaf = (int)((n + nl - 1) / nl);
     const int s = Omega ? s_in : (int)c->opt_s;
     if (s < 1) return HSS_EINVAL;
     const int s_pad = (int)round_up(s, 128);
@@ -265,8 +273,6 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     if (kcap > 512) return HSS_EUNSUPPORTED;
     int width = adaptive ? (int)c->opt_adapt_start : s;
     if (adaptive && cap_at(width) < 1) return HSS_EINVAL;
-    int L = 0;
-    while ((int64_t(1) << L) < nl) ++L;
 
     hipStream_t st = c->stream;
     c->compressed = c->factored = c->basis_cached = false;
@@ -364,28 +370,30 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
 
     // ---- leaf level: D_t and S_t = S - D Omega ----
     t0 = wall();
-    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)n * leaf));
+    c->doff.assign(nl + 1, 0);
+    for (int64_t t = 0; t < nl; ++t) c->doff[t + 1] = c->doff[t] + (loff[t + 1] - loff[t]) * (loff[t + 1] - loff[t]);
+    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)c->doff[nl]));
     // columns [c0, c1) of the leaf sample rows:  S_t -= D_t Omega_t
     auto leaf_columns = [&](int c0, int c1) -> int {
         Level& lv = c->lev[L];
         std::vector<GemmItem> gm(lv.N);
         const int w = (int)round_up(c1 - c0, 128);
         for (int t = 0; t < lv.N; ++t)
-            gm[t] = GemmItem{c->Dleaf.as<double>() + (size_t)t * leaf * leaf, Ob[0].as<double>() + (size_t)t * leaf * LD + c0,
-                             Sb[0].as<double>() + (size_t)t * leaf * LD + c0, leaf, w, leaf, leaf, LD, LD};
+            gm[t] = GemmItem{c->Dleaf.as<double>() + c->doff[t], Ob[0].as<double>() + (size_t)lv.moff[t] * LD + c0,
+                             Sb[0].as<double>() + (size_t)lv.moff[t] * LD + c0, lv.msz[t], w, lv.msz[t], lv.msz[t], LD, LD};
         return bgemm_host(st, c->arena, gm, false, false, -1.0, 1.0);
     };
     {
         Level& lv = c->lev[L];
         lv.N = (int)nl;
-        lv.msz.assign(lv.N, leaf);
-        lv.moff.resize(lv.N + 1);
-        for (int t = 0; t <= lv.N; ++t) lv.moff[t] = (int64_t)t * leaf;
-        lv.maxm = leaf;
+        lv.msz.resize(lv.N);
+        lv.moff = loff;
+        for (int t = 0; t < lv.N; ++t) lv.msz[t] = (int)(loff[t + 1] - loff[t]);
+        lv.maxm = maxleaf;
         std::vector<KBItem> kb(lv.N);
         for (int t = 0; t < lv.N; ++t)
-            kb[t] = KBItem{nullptr, nullptr, (int64_t)t * leaf, (int64_t)t * leaf,
-                           c->Dleaf.as<double>() + (size_t)t * leaf * leaf, leaf, leaf, leaf, 0};
+            kb[t] = KBItem{nullptr, nullptr, loff[t], loff[t], c->Dleaf.as<double>() + c->doff[t], lv.msz[t], lv.msz[t],
+                           lv.msz[t], 0};
         HSS_TRY(kernel_blocks(st, c->arena, kb, c->Fp.as<double>(), r_pad, h));
         if (L >= 1 && !ann) HSS_TRY(leaf_columns(0, width));
     }
@@ -459,7 +467,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
             for (int t = 0; t < N; ++t)
                 for (int64_t q = lv.moff[t]; q < lv.moff[t + 1]; ++q) rownode[(size_t)q] = t;
             const int64_t* rowpoint = l == L ? nullptr : c->lev[l + 1].skel.as<int64_t>();
-            HSS_TRY(ann_select_columns(c, ann_work, rowpoint, rownode, rows, N, n >> l, s, ann_cols.as<int64_t>(), ncols));
+            HSS_TRY(ann_select_columns(c, ann_work, rowpoint, rownode, rows, N, l, s, ann_cols.as<int64_t>(), ncols));
             HSS_TRY(fill_launch(st, Acur, rows * (int64_t)LD, 0.0));
             std::vector<KBItem> kb(N);
             for (int t = 0; t < N; ++t)
@@ -591,9 +599,9 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
         Level& rl = c->lev[0];
         if (L == 0) {
             rl.N = 1;
-            rl.msz.assign(1, leaf);
-            rl.moff = {0, leaf};
-            rl.maxm = leaf;
+            rl.msz.assign(1, (int)n);
+            rl.moff = {0, n};
+            rl.maxm = (int)n;
         }
         rl.rk.assign(1, 0);
         rl.koff = {0, 0};
@@ -604,7 +612,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     c->arena.reset();
     c->t_levels = wall() - t0;
 
-    c->generator_bytes = (int64_t)sizeof(double) * n * leaf;
+    c->generator_bytes = (int64_t)sizeof(double) * c->doff[nl];
     for (int l = 0; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (l >= 1) c->generator_bytes += (int64_t)sizeof(double) * lv.uoff[lv.N];
@@ -627,12 +635,12 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
                     const int32_t* J, const double* B, double delta) {
     if (!c || !F || !y || !perm_h || !sizes || !ranks || !D || !U || !J || !B) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(delta >= 0.0) || !(delta <= 1.7976931348623157e308)) return HSS_EINVAL;
-    if (leaf < 16 || leaf % 16 != 0 || n % leaf != 0) return HSS_EINVAL;
-    const int64_t nl = n / leaf;
-    if (nl & (nl - 1)) return HSS_EINVAL;
+    if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
     if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
-    int L = 0;
-    while ((int64_t(1) << L) < nl) ++L;
+    const int L = tree_depth(n, leaf);
+    if (L > 24) return HSS_EUNSUPPORTED;
+    const int64_t nl = int64_t(1) << L;
+    const std::vector<int64_t> loff = level_offsets(n, L);   // rows of leaf t: loff[t] .. loff[t+1]-1
     // ---- host-side validation of the tree arrays ----
     {
         std::vector<char> seen(n, 0);
@@ -649,7 +657,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
             for (int64_t t = 0; t < (int64_t(1) << l); ++t) {
                 const int64_t node = (int64_t(1) << l) - 1 + t;
                 const int m = sizes[node], k = ranks[node];
-                if (l == L ? m != leaf : m != ranks[2 * node + 1] + ranks[2 * node + 2]) return HSS_EINVAL;
+                if (l == L ? m != loff[t + 1] - loff[t] : m != ranks[2 * node + 1] + ranks[2 * node + 2]) return HSS_EINVAL;
                 if (l == 0) {
                     if (k != 0) return HSS_EINVAL;
                     continue;
@@ -702,8 +710,10 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
     HSS_TRY(gather_pad_rows_launch(st, F, perm, c->Fp.as<double>(), n, c->n_pad, r, c->r_pad));
     HSS_TRY(row_norms_launch(st, c->Fp.as<double>(), c->nu.as<double>(), c->n_pad, c->r_pad));
     HSS_TRY(vec_gather(st, c->yp.as<double>(), y, perm, n));
-    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)n * leaf));
-    HIP_TRY(hipMemcpyAsync(c->Dleaf.p, D, sizeof(double) * (size_t)n * leaf, hipMemcpyHostToDevice, st));
+    c->doff.assign(nl + 1, 0);
+    for (int64_t t = 0; t < nl; ++t) c->doff[t + 1] = c->doff[t] + (loff[t + 1] - loff[t]) * (loff[t + 1] - loff[t]);
+    HSS_TRY(c->Dleaf.reserve(sizeof(double) * (size_t)c->doff[nl]));
+    HIP_TRY(hipMemcpyAsync(c->Dleaf.p, D, sizeof(double) * (size_t)c->doff[nl], hipMemcpyHostToDevice, st));
     // ---- levels: sizes, offsets, generators; skeleton points rebuilt from the skeleton rows ----
     int64_t uo = 0, jo = 0, bo = 0;
     std::vector<std::vector<int64_t>> skel(L + 1);
@@ -766,7 +776,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
             HIP_TRY(hipMemcpyAsync(lv.skel.p, skel[l].data(), sizeof(int64_t) * skel[l].size(), hipMemcpyHostToDevice, st));
         }
     }
-    c->generator_bytes = (int64_t)sizeof(double) * n * leaf;
+    c->generator_bytes = (int64_t)sizeof(double) * c->doff[nl];
     for (int l = 0; l <= L; ++l) {
         Level& lv = c->lev[l];
         if (l >= 1) c->generator_bytes += (int64_t)sizeof(double) * lv.uoff[lv.N];

@@ -8,8 +8,8 @@
 //
 // One level = five small kernels (two-pass variance with per-chunk partial sums recombined in a fixed
 // order, so the result does not depend on scheduling) and one device-wide merge sort of 16-byte keys
-// (node, value, original index): nodes are contiguous equal-width ranges of the index array, so sorting
-// the whole array by that key sorts every node in place.
+// (node, value, original index): nodes are contiguous ranges of the index array (offsets in `noff`; shape of the
+// tree: see tree_depth), so sorting the whole array by that key sorts every node in place.
 #include "common.h"
 #include "ctx.h"
 #include <rocprim/device/device_merge_sort.hpp>
@@ -43,7 +43,8 @@ __global__ __launch_bounds__(256) void tree_iota_kernel(int64_t* idx, int64_t n)
 // (F[idx][c] - mean[node][c])^2 (MODE 1).  Thread t works on coordinate t % r of every (256 / r)-th point.
 template <int MODE>
 __global__ __launch_bounds__(256) void tree_partial_kernel(const double* __restrict__ F, int r,
-                                                           const int64_t* __restrict__ idx, int64_t w, int chunks,
+                                                           const int64_t* __restrict__ idx,
+                                                           const int64_t* __restrict__ noff, int chunks,
                                                            const double* __restrict__ mean, double* __restrict__ partial) {
     const int64_t node = blockIdx.x / chunks;
     const int ch = blockIdx.x % chunks;
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void tree_partial_kernel(const double* __restr
     const int c = threadIdx.x % r, pl = threadIdx.x / r;
     __shared__ double red[256];
     double acc = 0.0;
-    const int64_t lo = node * w + (int64_t)ch * TREE_CHUNK;
-    const int64_t hi = lo + TREE_CHUNK < (node + 1) * w ? lo + TREE_CHUNK : (node + 1) * w;
+    const int64_t lo = noff[node] + (int64_t)ch * TREE_CHUNK, end = noff[node + 1];   // lo >= end: an empty chunk
+    const int64_t hi = lo + TREE_CHUNK < end ? lo + TREE_CHUNK : end;
     if (pl < npl) {
         const double m = MODE ? mean[node * r + c] : 0.0;
         for (int64_t i = lo + pl; i < hi; i += npl) {
@@ -69,15 +70,15 @@ __global__ __launch_bounds__(256) void tree_partial_kernel(const double* __restr
     }
 }
 
-// mean[node][c] = (sum of the node's partials, in chunk order) / w
-__global__ __launch_bounds__(128) void tree_mean_kernel(const double* __restrict__ partial, int r, int chunks, double w,
-                                                        double* __restrict__ mean) {
+// mean[node][c] = (sum of the node's partials, in chunk order) / (points of the node)
+__global__ __launch_bounds__(128) void tree_mean_kernel(const double* __restrict__ partial, int r, int chunks,
+                                                        const int64_t* __restrict__ noff, double* __restrict__ mean) {
     const int c = threadIdx.x;
     if (c >= r) return;
     const double* p = partial + (size_t)blockIdx.x * chunks * r + c;
     double s = 0.0;
     for (int ch = 0; ch < chunks; ++ch) s += p[(size_t)ch * r];
-    mean[(size_t)blockIdx.x * r + c] = s / w;
+    mean[(size_t)blockIdx.x * r + c] = s / (double)(noff[blockIdx.x + 1] - noff[blockIdx.x]);
 }
 
 // best[node] = lowest coordinate whose summed squared deviation reaches (1 - 1e-9) x the largest.  A sum that is
@@ -106,11 +107,11 @@ __global__ __launch_bounds__(128) void tree_best_kernel(const double* __restrict
 }
 
 __global__ __launch_bounds__(256) void tree_keys_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
-                                                        int64_t n, int64_t w, const int* __restrict__ best,
-                                                        TreeKey* __restrict__ keys) {
+                                                        int64_t n, const int64_t* __restrict__ noff, int64_t nodes,
+                                                        const int* __restrict__ best, TreeKey* __restrict__ keys) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     const int64_t o = idx[i];
     const double v = F[o * r + best[node]];
     keys[i] = TreeKey{v, (node << SEG_SHIFT) | o};
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(256) void tm_amax_kernel(const double* __restrict__
 // qsum[(node*2 + side)*r + c] += sum of rint(F * scale) over the chunk's points on that side; cnt[node*2 + side]
 // += their number.  side == nullptr: every point counts as side 0.
 __global__ __launch_bounds__(256) void tm_sum_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
-                                                     int64_t w, int chunks, double scale,
+                                                     const int64_t* __restrict__ noff, int chunks, double scale,
                                                      const unsigned char* __restrict__ side, u64* __restrict__ qsum,
                                                      u64* __restrict__ cnt) {
     const int64_t node = blockIdx.x / chunks;
@@ -174,8 +175,8 @@ __global__ __launch_bounds__(256) void tm_sum_kernel(const double* __restrict__ 
     const int c = threadIdx.x % r, pl = threadIdx.x / r;
     __shared__ long long red[2][256];
     long long acc0 = 0, acc1 = 0, n0 = 0, n1 = 0;
-    const int64_t lo = node * w + (int64_t)ch * TREE_CHUNK;
-    const int64_t hi = lo + TREE_CHUNK < (node + 1) * w ? lo + TREE_CHUNK : (node + 1) * w;
+    const int64_t lo = noff[node] + (int64_t)ch * TREE_CHUNK, end = noff[node + 1];   // lo >= end: an empty chunk
+    const int64_t hi = lo + TREE_CHUNK < end ? lo + TREE_CHUNK : end;
     if (pl < npl) {
         for (int64_t i = lo + pl; i < hi; i += npl) {
             const long long q = (long long)rint(F[idx[i] * r + c] * scale);
@@ -227,22 +228,24 @@ __global__ __launch_bounds__(128) void tm_centre_kernel(const u64* __restrict__ 
 
 // d2[i] = dist2(point i, centre 0 of its node); dmax[node] = max of their bit patterns
 __global__ __launch_bounds__(256) void tm_far1_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
-                                                      int64_t n, int64_t w, const double* __restrict__ ctr,
-                                                      double* __restrict__ d2, u64* __restrict__ dmax) {
+                                                      int64_t n, const int64_t* __restrict__ noff, int64_t nodes,
+                                                      const double* __restrict__ ctr, double* __restrict__ d2,
+                                                      u64* __restrict__ dmax) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     const double v = dist2_seq(F + idx[i] * r, ctr + (size_t)(node * 2) * r, r);
     d2[i] = v;
     atomicMax(dmax + node, (u64)__double_as_longlong(v));
 }
 // amin[node] = lowest original index among the points that reach the maximum
-__global__ __launch_bounds__(256) void tm_far2_kernel(const int64_t* __restrict__ idx, int64_t n, int64_t w,
+__global__ __launch_bounds__(256) void tm_far2_kernel(const int64_t* __restrict__ idx, int64_t n,
+                                                      const int64_t* __restrict__ noff, int64_t nodes,
                                                       const double* __restrict__ d2, const u64* __restrict__ dmax,
                                                       u64* __restrict__ amin) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     if ((u64)__double_as_longlong(d2[i]) == dmax[node]) atomicMin(amin + node, (u64)idx[i]);
 }
 // centre `which` of every node = the point amin[node]
@@ -254,11 +257,11 @@ __global__ __launch_bounds__(128) void tm_take_point_kernel(const double* __rest
 }
 // side[i] = 0 if dist2(point, ca) <= dist2(point, cb) else 1
 __global__ __launch_bounds__(256) void tm_assign_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
-                                                        int64_t n, int64_t w, const double* __restrict__ ctr,
-                                                        unsigned char* __restrict__ side) {
+                                                        int64_t n, const int64_t* __restrict__ noff, int64_t nodes,
+                                                        const double* __restrict__ ctr, unsigned char* __restrict__ side) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     const double* x = F + idx[i] * r;
     const double da = dist2_seq(x, ctr + (size_t)(node * 2) * r, r);
     const double db = dist2_seq(x, ctr + (size_t)(node * 2 + 1) * r, r);
@@ -266,11 +269,11 @@ __global__ __launch_bounds__(256) void tm_assign_kernel(const double* __restrict
 }
 // sort key of point i: (node, sum_f (x_f - ca_f) (cb_f - ca_f), original index)
 __global__ __launch_bounds__(256) void tm_keys_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
-                                                      int64_t n, int64_t w, const double* __restrict__ ctr,
-                                                      TreeKey* __restrict__ keys) {
+                                                      int64_t n, const int64_t* __restrict__ noff, int64_t nodes,
+                                                      const double* __restrict__ ctr, TreeKey* __restrict__ keys) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
-    const int64_t node = i / w;
+    const int64_t node = segment_of(noff, nodes, i);
     const int64_t o = idx[i];
     const double* x = F + o * r;
     const double* ca = ctr + (size_t)(node * 2) * r;
@@ -282,6 +285,27 @@ __global__ __launch_bounds__(256) void tm_keys_kernel(const double* __restrict__
         p = p + t;
     }
     keys[i] = TreeKey{p, (node << SEG_SHIFT) | o};
+}
+
+// Node offsets of the levels 0 .. L-1 of the tree over n points, level after level, in device memory (level l at
+// d + start[l], 2^l + 1 entries).  The host copy lives as long as the object: the upload is asynchronous.
+struct LevelOffsets {
+    DevBuf d;
+    std::vector<int64_t> h;
+    std::vector<size_t> start;
+    const int64_t* level(int l) const { return d.as<int64_t>() + start[l]; }
+};
+int upload_level_offsets(hipStream_t st, int64_t n, int L, LevelOffsets& lo) {
+    lo.h.clear();
+    lo.start.assign(L, 0);
+    for (int l = 0; l < L; ++l) {
+        const std::vector<int64_t> off = level_offsets(n, l);
+        lo.start[l] = lo.h.size();
+        lo.h.insert(lo.h.end(), off.begin(), off.end());
+    }
+    HSS_TRY(lo.d.reserve(sizeof(int64_t) * std::max<size_t>(lo.h.size(), 1)));
+    if (!lo.h.empty()) HIP_TRY(hipMemcpyAsync(lo.d.p, lo.h.data(), sizeof(int64_t) * lo.h.size(), hipMemcpyHostToDevice, st));
+    return HSS_OK;
 }
 
 }  // namespace
@@ -308,11 +332,14 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
         HIP_TRY(hipStreamSynchronize(st));
         return HSS_OK;
     }
-    if (n <= leaf) return HSS_OK;
+    const int L = tree_depth(n, leaf);
+    if (L == 0) return HSS_OK;
     int e = 0;
     if (amax > 0.0) (void)frexp(amax, &e);          // amax < 2^e
     const double scale = ldexp(1.0, 38 - e);
-    const int64_t maxnodes = n / (2 * (int64_t)leaf) + 1;
+    const int64_t maxnodes = int64_t(1) << (L - 1);
+    LevelOffsets lo;
+    HSS_TRY(upload_level_offsets(st, n, L, lo));
     DevBuf qsum, cnt, ctr, dmax, amin, d2, side, keys_a, keys_b, tmp;
     HSS_TRY(qsum.reserve(sizeof(u64) * (size_t)maxnodes * 2 * r));
     HSS_TRY(cnt.reserve(sizeof(u64) * (size_t)maxnodes * 2));
@@ -326,14 +353,16 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
     size_t tmp_bytes = 0;
     HIP_TRY(rocprim::merge_sort(nullptr, tmp_bytes, keys_a.as<TreeKey>(), keys_b.as<TreeKey>(), (size_t)n, TreeKeyLess(), st));
     HSS_TRY(tmp.reserve(std::max<size_t>(tmp_bytes, 16)));
-    for (int64_t w = n; w > leaf; w /= 2) {
-        const int64_t nodes = n / w;
+    for (int l = 0; l < L; ++l) {
+        const int64_t nodes = int64_t(1) << l;
+        const int64_t w = (n + nodes - 1) / nodes;                   // the largest node of the level
         const int chunks = (int)((w + TREE_CHUNK - 1) / TREE_CHUNK);
         const unsigned grid = (unsigned)(nodes * chunks);
+        const int64_t* noff = lo.level(l);
         auto sums = [&](const unsigned char* sd, int both) -> int {
             HIP_TRY(hipMemsetAsync(qsum.p, 0, sizeof(u64) * (size_t)nodes * 2 * r, st));
             HIP_TRY(hipMemsetAsync(cnt.p, 0, sizeof(u64) * (size_t)nodes * 2, st));
-            hipLaunchKernelGGL(tm_sum_kernel, dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, w, chunks, scale, sd,
+            hipLaunchKernelGGL(tm_sum_kernel, dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks, scale, sd,
                                qsum.as<u64>(), cnt.as<u64>());
             hipLaunchKernelGGL(tm_centre_kernel, dim3((unsigned)nodes), dim3(128), 0, st, qsum.as<u64>(), cnt.as<u64>(), r,
                                scale, both, ctr.as<double>());
@@ -343,10 +372,10 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
         auto farthest_into = [&](int which) -> int {      // centre `which` = the point farthest from centre 0
             HIP_TRY(hipMemsetAsync(dmax.p, 0, sizeof(u64) * (size_t)nodes, st));
             HIP_TRY(hipMemsetAsync(amin.p, 0xff, sizeof(u64) * (size_t)nodes, st));
-            hipLaunchKernelGGL(tm_far1_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, w, ctr.as<double>(),
-                               d2.as<double>(), dmax.as<u64>());
-            hipLaunchKernelGGL(tm_far2_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n, w, d2.as<double>(), dmax.as<u64>(),
-                               amin.as<u64>());
+            hipLaunchKernelGGL(tm_far1_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, noff, nodes,
+                               ctr.as<double>(), d2.as<double>(), dmax.as<u64>());
+            hipLaunchKernelGGL(tm_far2_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n, noff, nodes, d2.as<double>(),
+                               dmax.as<u64>(), amin.as<u64>());
             hipLaunchKernelGGL(tm_take_point_kernel, dim3((unsigned)nodes), dim3(128), 0, st, F_dev, r, amin.as<u64>(), which,
                                ctr.as<double>());
             HIP_TRY(hipGetLastError());
@@ -356,12 +385,12 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
         HSS_TRY(farthest_into(0));          // centre 0 = a
         HSS_TRY(farthest_into(1));          // centre 1 = b
         for (int it = 0; it < iters; ++it) {
-            hipLaunchKernelGGL(tm_assign_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, w, ctr.as<double>(),
-                               side.as<unsigned char>());
+            hipLaunchKernelGGL(tm_assign_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, noff, nodes,
+                               ctr.as<double>(), side.as<unsigned char>());
             HSS_TRY(sums(side.as<unsigned char>(), 1));
         }
-        hipLaunchKernelGGL(tm_keys_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, w, ctr.as<double>(),
-                           keys_a.as<TreeKey>());
+        hipLaunchKernelGGL(tm_keys_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, noff, nodes,
+                           ctr.as<double>(), keys_a.as<TreeKey>());
         HIP_TRY(hipGetLastError());
         HIP_TRY(rocprim::merge_sort(tmp.p, tmp_bytes, keys_a.as<TreeKey>(), keys_b.as<TreeKey>(), (size_t)n, TreeKeyLess(), st));
         hipLaunchKernelGGL(tree_unpack_kernel, dim3(nb), dim3(256), 0, st, keys_b.as<TreeKey>(), n, perm_dev);
@@ -371,38 +400,44 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
     return HSS_OK;
 }
 
-// perm_dev[i] = original index of the i-th point in leaf order.  n = leaf * 2^L, F_dev is n x r row-major.
+// perm_dev[i] = original index of the i-th point in leaf order.  F_dev is n x r row-major; any n >= 1.
 // *bad_dev (an int the caller zeroed) is set when F holds a value that is not finite.
 int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int64_t* perm_dev, int* bad_dev) {
     if (r < 1 || r > 128 || n < 1 || n >= (int64_t(1) << SEG_SHIFT)) return HSS_EINVAL;
     const unsigned nb = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(tree_iota_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n);
     HIP_TRY(hipGetLastError());
-    if (n <= leaf) return HSS_OK;
+    const int L = tree_depth(n, leaf);
+    if (L == 0) return HSS_OK;
     DevBuf partial, mean, best, keys_a, keys_b, tmp;
-    const int64_t max_blocks = (n + TREE_CHUNK - 1) / TREE_CHUNK + n / (2 * (int64_t)leaf) + 1;
+    const int64_t maxnodes = int64_t(1) << (L - 1);
+    const int64_t max_blocks = (n + TREE_CHUNK - 1) / TREE_CHUNK + 2 * maxnodes;   // sum over nodes of ceil(size / chunk)
+    LevelOffsets lo;
+    HSS_TRY(upload_level_offsets(st, n, L, lo));
     HSS_TRY(partial.reserve(sizeof(double) * (size_t)max_blocks * r));
-    HSS_TRY(mean.reserve(sizeof(double) * (size_t)(n / leaf) * r));
-    HSS_TRY(best.reserve(sizeof(int) * (size_t)(n / leaf)));
+    HSS_TRY(mean.reserve(sizeof(double) * (size_t)maxnodes * r));
+    HSS_TRY(best.reserve(sizeof(int) * (size_t)maxnodes));
     HSS_TRY(keys_a.reserve(sizeof(TreeKey) * (size_t)n));
     HSS_TRY(keys_b.reserve(sizeof(TreeKey) * (size_t)n));
     size_t tmp_bytes = 0;
     HIP_TRY(rocprim::merge_sort(nullptr, tmp_bytes, keys_a.as<TreeKey>(), keys_b.as<TreeKey>(), (size_t)n, TreeKeyLess(), st));
     HSS_TRY(tmp.reserve(std::max<size_t>(tmp_bytes, 16)));
-    for (int64_t w = n; w > leaf; w /= 2) {
-        const int64_t nodes = n / w;
+    for (int l = 0; l < L; ++l) {
+        const int64_t nodes = int64_t(1) << l;
+        const int64_t w = (n + nodes - 1) / nodes;                   // the largest node of the level
         const int chunks = (int)((w + TREE_CHUNK - 1) / TREE_CHUNK);
         const unsigned grid = (unsigned)(nodes * chunks);
-        hipLaunchKernelGGL((tree_partial_kernel<0>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, w, chunks,
+        const int64_t* noff = lo.level(l);
+        hipLaunchKernelGGL((tree_partial_kernel<0>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks,
                            (const double*)nullptr, partial.as<double>());
         hipLaunchKernelGGL(tree_mean_kernel, dim3((unsigned)nodes), dim3(128), 0, st, partial.as<double>(), r, chunks,
-                           (double)w, mean.as<double>());
-        hipLaunchKernelGGL((tree_partial_kernel<1>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, w, chunks,
+                           noff, mean.as<double>());
+        hipLaunchKernelGGL((tree_partial_kernel<1>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks,
                            mean.as<double>(), partial.as<double>());
         hipLaunchKernelGGL(tree_best_kernel, dim3((unsigned)nodes), dim3(128), 0, st, partial.as<double>(), r, chunks,
                            best.as<int>(), bad_dev);
-        hipLaunchKernelGGL(tree_keys_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, w, best.as<int>(),
-                           keys_a.as<TreeKey>());
+        hipLaunchKernelGGL(tree_keys_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, noff, nodes,
+                           best.as<int>(), keys_a.as<TreeKey>());
         HIP_TRY(hipGetLastError());
         HIP_TRY(rocprim::merge_sort(tmp.p, tmp_bytes, keys_a.as<TreeKey>(), keys_b.as<TreeKey>(), (size_t)n, TreeKeyLess(), st));
         hipLaunchKernelGGL(tree_unpack_kernel, dim3(nb), dim3(256), 0, st, keys_b.as<TreeKey>(), n, perm_dev);

@@ -248,7 +248,7 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
     if (!c->compressed) return HSS_ESTATE;
     if (!(beta > 0.0)) return HSS_EINVAL;
     hipStream_t st = c->stream;
-    const int L = c->L, leaf = c->leaf;
+    const int L = c->L;
     const double shift = c->delta + beta;
     const double tiny = 1e-12 * std::max(1.0, shift);
     c->factored = false;
@@ -261,11 +261,11 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
     // leaf blocks D + shift I
     {
         Level& lv = c->lev[L];
-        HSS_TRY(Dbuf[cur].reserve(sizeof(double) * (size_t)c->n * leaf));
+        HSS_TRY(Dbuf[cur].reserve(sizeof(double) * (size_t)c->doff[lv.N]));
         std::vector<CopyItem> ci(lv.N);
         for (int t = 0; t < lv.N; ++t)
-            ci[t] = cp(c->Dleaf.as<double>() + (size_t)t * leaf * leaf, Dbuf[cur].as<double>() + (size_t)t * leaf * leaf,
-                       leaf, leaf, leaf, leaf, COPY_PLAIN_ADD_DIAG, shift);
+            ci[t] = cp(c->Dleaf.as<double>() + c->doff[t], Dbuf[cur].as<double>() + c->doff[t], lv.msz[t], lv.msz[t],
+                       lv.msz[t], lv.msz[t], COPY_PLAIN_ADD_DIAG, shift);
         HSS_TRY(bcopy(st, c->arena, ci));
     }
     int64_t bytes_solve = 0, bytes_compact = 0;

@@ -52,7 +52,8 @@ def oracle_hss_from_export(exp, with_shift=True):
         H.B[t] = exp["B"][bo:bo + ka * kb].reshape(ka, kb).copy()
         bo += ka * kb
     shift = exp["delta"] if with_shift else 0.0
-    H.D = [exp["D"][i] + shift * np.eye(leaf) for i in range(n // leaf)]
+    H.D = [exp["D"][i] + shift * np.eye(exp["D"][i].shape[0]) for i in range(len(exp["D"]))]
+    assert [d.shape[0] for d in H.D] == list(np.diff(H.loff))
     assert uo == exp["U"].size and bo == exp["B"].size
     return H
 
@@ -67,5 +68,5 @@ def export_from_oracle_hss(H, perm, delta=0.0):
     B = [H.B[t].reshape(-1) for t in range(H.first_leaf())]
     cat = lambda xs, dt: np.concatenate(xs).astype(dt) if xs else np.zeros(0, dtype=dt)
     return {"n": H.n, "leaf": H.leaf, "perm": np.asarray(perm, dtype=np.int64), "sizes": sizes, "ranks": ranks,
-            "D": np.stack(H.D), "U": cat(U, np.float64), "J": cat(J, np.int32), "B": cat(B, np.float64),
+            "D": np.stack(H.D) if len({d.shape for d in H.D}) == 1 else list(H.D), "U": cat(U, np.float64), "J": cat(J, np.int32), "B": cat(B, np.float64),
             "delta": float(delta)}
