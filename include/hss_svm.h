@@ -162,7 +162,8 @@ int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y
 /* Achieved compression error, estimated on nprobe (1..128) Gaussian probe vectors z_j drawn by the library's
  * counter-based generator from `seed`:  sqrt( sum_j ||K~ z_j - K z_j||^2 / sum_j ||K z_j||^2 ), an estimate of
  * ||K~ - K||_F / ||K||_F (the quantity the tolerance of Sec. 3.2 / eq. (9) speaks of), with K z_j from the exact
- * kernel (one pass of the sampling kernel over a 128-column block) and K~ without the guard's shift.
+ * kernel (one pass of the fused kernel product: its 16-column form up to 16 probes, 128-column blocks of the sampling
+ * kernel beyond) and K~ without the guard's shift.
  * rel_err_out (host).  Needs a compressed context.  Synchronous. */
 int hss_error_estimate(hss_ctx* ctx, int32_t nprobe, uint64_t seed, double* rel_err_out);
 

@@ -117,15 +117,20 @@ int hss_error_estimate(hss_ctx* c, int32_t nprobe, uint64_t seed, double* rel_er
     if (!c->compressed) return HSS_ESTATE;
     hipStream_t st = c->stream;
     const int64_t n = c->n, n_pad = c->n_pad;
-    const int sp = 128;                               // narrowest block the sampling kernel takes
-    DevBuf Z, KZ, t, r;
+    // K Z through the 16-column product when the probes fit, else through a 128-column block of the sampling kernel
+    const int sp = nprobe <= 16 ? 16 : 128;
+    DevBuf Z, KZ, t, r, work;
     HSS_TRY(Z.reserve(sizeof(double) * n_pad * sp));
     HSS_TRY(KZ.reserve(sizeof(double) * n_pad * sp));
     HSS_TRY(t.reserve(sizeof(double) * n));
     HSS_TRY(r.reserve(sizeof(double) * n));
     HSS_TRY(omega_fill_launch(st, Z.as<double>(), n, n_pad, nprobe, sp, seed));
-    HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Z.as<double>(), KZ.as<double>(), n_pad, c->r_pad, sp,
-                          c->h));
+    if (sp == 16)
+        HSS_TRY(sample_narrow_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(), c->nu.as<double>(),
+                                     n_pad, Z.as<double>(), KZ.as<double>(), c->r_pad, c->h, work));
+    else
+        HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Z.as<double>(), KZ.as<double>(), n_pad, c->r_pad,
+                              sp, c->h));
     double* part = c->partial.as<double>();
     double* scal = c->scal.as<double>();
     double num = 0.0, den = 0.0;
@@ -309,11 +314,11 @@ int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, d
     if (n_test == 0) return HSS_OK;
     hipStream_t st = c->stream;
     // dec = K(G, F) (y .* z) + b is the sampling product with the test points as rows, the training points as
-    // columns and one "random" column y .* z: the same fused Gram + exp + contraction kernel, on a block of 128
-    // columns of which the first is used
-    const int sp = 128;
+    // columns and one "random" column y .* z: the fused Gram + exp + contraction in its 16-column form, of which
+    // the first column is used
+    const int sp = 16;
     const int64_t nt_pad = round_up(n_test, 256);
-    DevBuf Gp, nug, Om, S;
+    DevBuf Gp, nug, Om, S, work;
     HSS_TRY(Gp.reserve(sizeof(double) * nt_pad * c->r_pad));
     HSS_TRY(nug.reserve(sizeof(double) * nt_pad));
     HSS_TRY(Om.reserve(sizeof(double) * c->n_pad * sp));
@@ -322,8 +327,8 @@ int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, d
     HSS_TRY(row_norms_launch(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->r_pad));
     HSS_TRY(fill_launch(st, Om.as<double>(), c->n_pad * sp, 0.0));
     HSS_TRY(zy_column(st, Om.as<double>(), sp, z, c->yp.as<double>(), c->perm.as<int64_t>(), c->n));
-    HSS_TRY(sample_launch_rect(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->Fp.as<double>(), c->nu.as<double>(),
-                               c->n_pad, Om.as<double>(), S.as<double>(), c->r_pad, sp, c->h));
+    HSS_TRY(sample_narrow_launch(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->Fp.as<double>(), c->nu.as<double>(),
+                                 c->n_pad, Om.as<double>(), S.as<double>(), c->r_pad, c->h, work));
     HSS_TRY(decision_finish(st, dec, S.as<double>(), sp, bias, n_test));
     HIP_TRY(hipStreamSynchronize(st));   // the temporaries are freed on return
     return HSS_OK;

@@ -164,6 +164,10 @@ int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int6
 int sample_launch_window(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
                          const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
                          double h);
+// S (nr_pad x 16) = K(rows, cols) V for a block V (n_pad x 16) of at most 16 used columns (sample_narrow.hip); `work`
+// is grown to hold partial results when the rows are few
+int sample_narrow_launch(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                         const double* nu, int64_t n_pad, const double* V, double* S, int r_pad, double h, DevBuf& work);
 int row_norms_launch(hipStream_t st, const double* Fp, double* nu, int64_t n_pad, int r_pad);
 // Fp[i, :] = F[perm[i], :] zero padded to r_pad columns; rows >= n are zeroed.  perm == nullptr: identity.
 int gather_pad_rows_launch(hipStream_t st, const double* F, const int64_t* perm, double* Fp, int64_t n, int64_t n_pad,

@@ -156,3 +156,27 @@ def test_wide_sample_1024_columns_rank_cap_512():
     err_or = np.linalg.norm(K - ohss.densify(Ho)) / np.linalg.norm(K)
     assert err <= max(w.tol, 1.5 * err_or), (err, err_or)
     ctx.close()
+
+
+@pytest.mark.parametrize("r,n,n_test", [(3, 1000, 1), (30, 3001, 100), (60, 2048, 5000), (96, 777, 300), (8, 20000, 64)])
+def test_label_assignment_shapes(r, n, n_test):
+    """Decision values (Algorithm 3, last line) against the oracle's direct sum over the exact kernel, for every
+    feature padding of the 16-column product (28, 56, 84, 112) and for row counts from one test point (the column
+    blocks split over the grid) to thousands; the error estimate on the same context, narrow (<= 16 probes) against
+    wide (the 128-column sampling block) on the same probe vectors."""
+    rng = np.random.default_rng(r * 1000 + n_test)
+    F = rng.standard_normal((n, r))
+    G = rng.standard_normal((n_test, r))
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    h = 0.7 * np.sqrt(r)
+    ctx = binding.Context()
+    ctx.hss_compress(_dev(F), _dev(y), h, 64, 1e-2)
+    z = rng.random(n)
+    z[rng.random(n) < 0.3] = 0.0
+    dec = ctx.svm_decision(_dev(G), _dev(z), 0.25).cpu().numpy()
+    ref = oadmm.decision(F, y, z, 0.25, G, h)
+    assert np.abs(dec - ref).max() <= 1e-10 * max(1.0, np.abs(ref).max())
+    e16 = ctx.hss_error_estimate(16, 5)
+    e17 = ctx.hss_error_estimate(17, 5)          # one more probe through the other kernel: nearly the same estimate
+    assert abs(e16 - e17) <= 0.25 * e17
+    ctx.close()
