@@ -148,7 +148,9 @@ int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int3
  * size, a multiple of 16 with 16 <= leaf <= 1024; 1 <= r <= 96, h > 0, 0 < tol < 1.
  * Shape of the tree: depth L = the smallest one with ceil(n / 2^L) <= leaf; a node of p points gives the lower
  * ceil(p/2) of them (in the order of its split) to the left child and the rest to the right one.  All leaves are on
- * level L and hold floor or ceil of n / 2^L points (n = leaf * 2^L: exactly `leaf` each).  Pivots of each decomposition are kept while
+ * level L and hold floor or ceil of n / 2^L points (n = leaf * 2^L: exactly `leaf` each).
+ * The kernel products work on the points minus their feature means (the kernel of Sec. 1.1 sees differences only;
+ * points far from the origin would otherwise lose digits in ||f_i||^2 + ||f_j||^2 - 2 f_i . f_j).  Pivots of each decomposition are kept while
  * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 and s <= 2048 (s <= 1024 for
  * tol < 3e-5), EUNSUPPORTED beyond.
  * Drops any previous compression and factorization held by the context.

@@ -75,19 +75,22 @@ __global__ __launch_bounds__(256) void list_clear_kernel(int32_t* __restrict__ i
     }
 }
 
-// Ft[f * n + pos] = Fp[order[pos] * r_pad + f]
-__global__ __launch_bounds__(256) void transpose_gather_kernel(const double* __restrict__ Fp, int r_pad, int r,
+// Ft[f * n + pos] = feature f of point order[pos] of the cluster-tree order, i.e. F[perm[order[pos]] * r + f]: the
+// caller's values as given (the centred copy differs from them in the last bits, and the lists are defined on these)
+__global__ __launch_bounds__(256) void transpose_gather_kernel(const double* __restrict__ F, int r,
+                                                               const int64_t* __restrict__ perm,
                                                                const int64_t* __restrict__ order, int64_t n,
                                                                double* __restrict__ Ft) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n * r) return;
     const int f = (int)(i / n);
     const int64_t pos = i - (int64_t)f * n;
-    Ft[i] = Fp[order[pos] * r_pad + f];
+    Ft[i] = F[perm[order[pos]] * r + f];
 }
 
 // key of position i: (node, sum_f x_f dir[node][f], point)
-__global__ __launch_bounds__(256) void proj_keys_kernel(const double* __restrict__ Fp, int r_pad, int r,
+__global__ __launch_bounds__(256) void proj_keys_kernel(const double* __restrict__ F, int r,
+                                                        const int64_t* __restrict__ perm,
                                                         const int64_t* __restrict__ order, int64_t n,
                                                         const int64_t* __restrict__ noff, int64_t nodes,
                                                         const double* __restrict__ dirs, PKey* __restrict__ keys) {
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(256) void proj_keys_kernel(const double* __restrict
     if (i >= n) return;
     const int64_t node = segment_of(noff, nodes, i);
     const int64_t o = order[i];
-    const double* x = Fp + o * r_pad;
+    const double* x = F + perm[o] * r;
     const double* d = dirs + node * r;
     double p = 0.0;
     for (int f = 0; f < r; ++f) {
@@ -277,10 +280,11 @@ double ann_direction_component(uint64_t seed, int tree, int level, int64_t node,
 }
 
 // Neighbour lists of the n points of the context (cluster-tree order) into c->nbr_idx / c->nbr_dist (n x k).
-int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
+int ann_search(hss_ctx* c, const double* F, int k, int cell, int trees, uint64_t seed) {
     hipStream_t st = c->stream;
     const int64_t n = c->n;
-    const int r = c->r, r_pad = c->r_pad;
+    const int r = c->r;
+    const int64_t* perm = c->perm.as<int64_t>();
     if (k < 1 || k > 64 || trees < 1 || cell < 2 || n >= (int64_t(1) << 31)) return HSS_EINVAL;
     // cells: the nodes of the deepest level of the cluster tree whose nodes all hold at least `cell` points (the
     // root if none does); every projection tree is split down to the same level
@@ -329,7 +333,7 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
                 for (int64_t node = 0; node < nodes; ++node)
                     for (int f = 0; f < r; ++f) dh[(size_t)node * r + f] = ann_direction_component(seed, t, level, node, f);
                 HIP_TRY(hipMemcpyAsync(dirs.p, dh.data(), sizeof(double) * dh.size(), hipMemcpyHostToDevice, st));
-                hipLaunchKernelGGL(proj_keys_kernel, dim3(nb), dim3(256), 0, st, c->Fp.as<double>(), r_pad, r,
+                hipLaunchKernelGGL(proj_keys_kernel, dim3(nb), dim3(256), 0, st, F, r, perm,
                                    order.as<int64_t>(), n, offd.as<int64_t>() + start[level], nodes, dirs.as<double>(),
                                    keys_a.as<PKey>());
                 HIP_TRY(hipGetLastError());
@@ -340,8 +344,8 @@ int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed) {
             }
         }
         const int64_t tot = n * r;
-        hipLaunchKernelGGL(transpose_gather_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, c->Fp.as<double>(),
-                           r_pad, r, order.as<int64_t>(), n, Ft.as<double>());
+        hipLaunchKernelGGL(transpose_gather_kernel, dim3((unsigned)((tot + 255) / 256)), dim3(256), 0, st, F, r, perm,
+                           order.as<int64_t>(), n, Ft.as<double>());
         hipLaunchKernelGGL(knn_cell_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, st, Ft.as<double>(), r, n,
                            order.as<int64_t>(), offd.as<int64_t>() + start[lc], ncells, k, c->nbr_idx.as<int32_t>(),
                            c->nbr_dist.as<double>());

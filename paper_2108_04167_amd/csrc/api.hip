@@ -80,13 +80,17 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
     hipStream_t st = ctx->stream;
     const int64_t n_pad = round_up(n, 256);
     const int r_pad = feature_pad(r), s_pad = (int)round_up(s, 128);
-    DevBuf Fp, nu, Om, S;
+    DevBuf Fp, nu, Om, S, mean;
     HSS_TRY(Fp.reserve(sizeof(double) * n_pad * r_pad));
     HSS_TRY(nu.reserve(sizeof(double) * n_pad));
     HSS_TRY(Om.reserve(sizeof(double) * n_pad * s_pad));
     HSS_TRY(S.reserve(sizeof(double) * n_pad * s_pad));
     HSS_TRY(gather_pad_rows_launch(st, F_dev, nullptr, Fp.as<double>(), n, n_pad, r, r_pad));
     HSS_TRY(gather_pad_rows_launch(st, Omega_dev, nullptr, Om.as<double>(), n, n_pad, s, s_pad));
+    // the points minus their mean (see vec.h); S itself serves as the work space of the means
+    HSS_TRY(mean.reserve(sizeof(double) * r));
+    HSS_TRY(column_means_launch(st, Fp.as<double>(), n, r, r_pad, S.as<double>(), mean.as<double>()));
+    HSS_TRY(centre_rows_launch(st, Fp.as<double>(), n, r, r_pad, mean.as<double>()));
     HSS_TRY(row_norms_launch(st, Fp.as<double>(), nu.as<double>(), n_pad, r_pad));
     HSS_TRY(sample_launch(st, Fp.as<double>(), nu.as<double>(), Om.as<double>(), S.as<double>(), n_pad, r_pad, s_pad, h));
     HIP_TRY(hipMemcpy2DAsync(S_out_dev, sizeof(double) * s, S.p, sizeof(double) * s_pad, sizeof(double) * s, n,
@@ -324,6 +328,7 @@ int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, d
     HSS_TRY(Om.reserve(sizeof(double) * c->n_pad * sp));
     HSS_TRY(S.reserve(sizeof(double) * nt_pad * sp));
     HSS_TRY(gather_pad_rows_launch(st, G, nullptr, Gp.as<double>(), n_test, nt_pad, c->r, c->r_pad));
+    HSS_TRY(centre_rows_launch(st, Gp.as<double>(), n_test, c->r, c->r_pad, c->centre.as<double>()));   // as the training points
     HSS_TRY(row_norms_launch(st, Gp.as<double>(), nug.as<double>(), nt_pad, c->r_pad));
     HSS_TRY(fill_launch(st, Om.as<double>(), c->n_pad * sp, 0.0));
     HSS_TRY(zy_column(st, Om.as<double>(), sp, z, c->yp.as<double>(), c->perm.as<int64_t>(), c->n));

@@ -75,7 +75,8 @@ struct hss_ctx {
     int warnings = 0;
     int width_used = 0;                     // sample columns the decompositions ended up using
     int64_t nodes_redone = 0;               // node decompositions repeated after widening the sample
-    DevBuf Fp, nu, yp, perm;
+    DevBuf Fp, nu, yp, perm;                // Fp: the points in cluster-tree order, centred (minus `centre`), zero padded
+    DevBuf centre;                          // r feature means of the training points (subtracted from test points too)
     DevBuf Dleaf;                           // leaf diagonal blocks D_t (m_t x m_t row-major), leaf t at doff[t]
     std::vector<int64_t> doff;              // prefix sums of m_t^2 over the leaves            [2^L + 1]
     bool leaves_even = false;               // every leaf size is even: 16-byte loads allowed on the D_t
@@ -113,7 +114,7 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
 // noalloc.hip: device address of the library's fixed scratch array on the current device
 int noalloc_scratch_for_current_device(double** out);
 // ann.hip
-int ann_search(hss_ctx* c, int k, int cell, int trees, uint64_t seed);
+int ann_search(hss_ctx* c, const double* F, int k, int cell, int trees, uint64_t seed);   // F: the caller's n x r points
 struct AnnWork {    // work buffers of ann_select_columns, reused across the levels of one compression
     DevBuf rn, keys_a, keys_b, tmp, seg_lo, seg_hi, ncd, span;
 };

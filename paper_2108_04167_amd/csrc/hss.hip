@@ -53,6 +53,17 @@ double tridiag_min_eig(const std::vector<double>& a, const std::vector<double>& 
     return 0.5 * (lo + hi);
 }
 
+// c->centre = feature means of the points in c->Fp, and Fp minus them (see vec.h)
+int centre_features(hss_ctx* c) {
+    DevBuf work;
+    HSS_TRY(work.reserve(sizeof(double) * centre_work_doubles(c->n, c->r)));
+    HSS_TRY(c->centre.reserve(sizeof(double) * c->r));
+    HSS_TRY(column_means_launch(c->stream, c->Fp.as<double>(), c->n, c->r, c->r_pad, work.as<double>(), c->centre.as<double>()));
+    HSS_TRY(centre_rows_launch(c->stream, c->Fp.as<double>(), c->n, c->r, c->r_pad, c->centre.as<double>()));
+    HIP_TRY(hipStreamSynchronize(c->stream));     // the work buffer is released on return
+    return HSS_OK;
+}
+
 int build_matvec_tables(hss_ctx* c) {
     hipStream_t st = c->stream;
     const int L = c->L;
@@ -316,6 +327,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     HSS_TRY(c->nu.reserve(sizeof(double) * n_pad));
     HSS_TRY(c->yp.reserve(sizeof(double) * n));
     HSS_TRY(gather_pad_rows_launch(st, F, perm, c->Fp.as<double>(), n, n_pad, r, r_pad));
+    HSS_TRY(centre_features(c));
     HSS_TRY(row_norms_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, r_pad));
     HSS_TRY(vec_gather(st, c->yp.as<double>(), y, perm, n));
     HIP_TRY(hipStreamSynchronize(st));
@@ -333,7 +345,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     if (!ann) HSS_TRY(Ob[0].reserve(nsbytes));
     t0 = wall();
     if (ann) {
-        HSS_TRY(ann_search(c, (int)c->opt_ann_k, (int)c->opt_ann_cell, (int)c->opt_ann_trees, (uint64_t)c->opt_seed));
+        HSS_TRY(ann_search(c, F, (int)c->opt_ann_k, (int)c->opt_ann_cell, (int)c->opt_ann_trees, (uint64_t)c->opt_seed));
     } else if (Omega) HSS_TRY(gather_pad_rows_launch(st, Omega, perm, Ob[0].as<double>(), n, n_pad, s, s_pad));
     else HSS_TRY(omega_fill_launch(st, Ob[0].as<double>(), n, n_pad, s, s_pad, (uint64_t)c->opt_seed));
     c->t_sample_kernel = 0.0;
@@ -708,6 +720,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
     HSS_TRY(c->nu.reserve(sizeof(double) * c->n_pad));
     HSS_TRY(c->yp.reserve(sizeof(double) * n));
     HSS_TRY(gather_pad_rows_launch(st, F, perm, c->Fp.as<double>(), n, c->n_pad, r, c->r_pad));
+    HSS_TRY(centre_features(c));
     HSS_TRY(row_norms_launch(st, c->Fp.as<double>(), c->nu.as<double>(), c->n_pad, c->r_pad));
     HSS_TRY(vec_gather(st, c->yp.as<double>(), y, perm, n));
     c->doff.assign(nl + 1, 0);

@@ -16,9 +16,10 @@ constexpr int     NA_MAX_S = 128;        // columns of Omega
 constexpr int64_t NA_NPAD = 4096;        // NA_MAX_N rounded up to the sampling kernel's row tile
 constexpr int     NA_RPAD = 112;         // feature_pad(NA_MAX_R)
 constexpr int     NA_SPAD = 128;
-// Fp (n_pad x r_pad) | nu (n_pad) | Omega (n_pad x s_pad) | S (n_pad x s_pad): 12.1 MB per GPU, held until
-// the process ends
-constexpr size_t  NA_DOUBLES = (size_t)NA_NPAD * (NA_RPAD + 1 + 2 * NA_SPAD);
+// Fp (n_pad x r_pad) | nu (n_pad) | Omega (n_pad x s_pad) | S (n_pad x s_pad) | feature means and their partial
+// sums (512): 12.1 MB per GPU, held until the process ends
+constexpr size_t  NA_MEAN_DOUBLES = 512;     // >= NA_MAX_R + centre_work_doubles(NA_MAX_N, NA_MAX_R) = 96 + 384
+constexpr size_t  NA_DOUBLES = (size_t)NA_NPAD * (NA_RPAD + 1 + 2 * NA_SPAD) + NA_MEAN_DOUBLES;
 
 static __device__ __align__(256) double scratch[NA_DOUBLES];
 
@@ -68,8 +69,11 @@ extern "C" int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int6
     double* nu = Fp + (size_t)NA_NPAD * NA_RPAD;
     double* Om = nu + NA_NPAD;
     double* S = Om + (size_t)NA_NPAD * NA_SPAD;
+    double* mean = S + (size_t)NA_NPAD * NA_SPAD;       // NA_MAX_R means, then the partial sums
     HSS_TRY(gather_pad_rows_launch(st, F_dev, nullptr, Fp, n, n_pad, r, r_pad));
     HSS_TRY(gather_pad_rows_launch(st, Omega_dev, nullptr, Om, n, n_pad, s, s_pad));
+    HSS_TRY(column_means_launch(st, Fp, n, r, r_pad, mean + NA_MAX_R, mean));
+    HSS_TRY(centre_rows_launch(st, Fp, n, r, r_pad, mean));
     HSS_TRY(row_norms_launch(st, Fp, nu, n_pad, r_pad));
     HSS_TRY(sample_launch(st, Fp, nu, Om, S, n_pad, r_pad, s_pad, h));
     const int64_t total = n * s;

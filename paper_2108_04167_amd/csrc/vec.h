@@ -37,3 +37,14 @@ int bias_sums(hipStream_t st, const double* z, const double* y, const double* u,
 int zy_column(hipStream_t st, double* Om, int ld, const double* z, const double* yp, const int64_t* perm, int64_t n);
 int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double bias, int64_t n_test);
 int stream_copy_launch(hipStream_t st, const double* src, double* dst, int64_t n);   // n even, 16-byte aligned
+
+// Centring of the feature rows before the kernel products (the Gaussian kernel sees differences of points only, so a
+// common shift changes nothing in exact arithmetic, while the expansion ||f_i||^2 + ||f_j||^2 - 2 f_i . f_j loses
+// as many digits as the norms exceed the distances by: data with an offset would lose them all).
+constexpr int CENTRE_ROWS = 1024;            // rows per partial sum
+inline int64_t centre_work_doubles(int64_t n, int r) { return (n + CENTRE_ROWS - 1) / CENTRE_ROWS * r; }
+// mean[c] = (sum over the first n rows of X[row * ld + c]) / n for c < r <= 256, partial sums of 1024 rows added in a
+// fixed order; work: centre_work_doubles(n, r) doubles
+int column_means_launch(hipStream_t st, const double* X, int64_t n, int r, int ld, double* work, double* mean);
+// X[row * ld + c] -= mean[c] for row < n, c < r
+int centre_rows_launch(hipStream_t st, double* X, int64_t n, int r, int ld, const double* mean);

@@ -180,3 +180,65 @@ def test_label_assignment_shapes(r, n, n_test):
     e17 = ctx.hss_error_estimate(17, 5)          # one more probe through the other kernel: nearly the same estimate
     assert abs(e16 - e17) <= 0.25 * e17
     ctx.close()
+
+
+@pytest.mark.parametrize("offset", [1e3, 1e6, -3e7])
+def test_features_with_a_large_common_offset(offset):
+    """The Gaussian kernel sees differences of points only.  The kernel products expand ||f_i - f_j||^2 into norms and
+    an inner product, which would lose log10(offset^2) digits on points far from the origin; the library subtracts
+    the feature means first, so the results must match the oracle (direct differences) as on centred data: S = K Omega
+    to 1e-12, the whole path on the exported matrix, and decision values for test points with the same offset."""
+    from gpu_helpers import oracle_hss_from_export
+    rng = np.random.default_rng(11)
+    n, r, h, leaf, s = 1500, 8, 1.5, 64, 128
+    F = rng.standard_normal((n, r)) + offset
+    G = rng.standard_normal((200, r)) + offset
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0)
+    Om = rng.standard_normal((n, s))
+    ctx = binding.Context()
+    S = ctx.hss_kernel_sample(_dev(F), h, _dev(Om)).cpu().numpy()
+    K = gaussian_kernel(F, F, h)
+    ref = K @ Om
+    assert np.abs(S - ref).max() <= 1e-12 * np.abs(ref).max()
+    import torch
+    Sn = torch.empty((n, s), dtype=torch.float64, device="cuda:0")
+    ctx.hss_kernel_sample_noalloc(_dev(F), h, _dev(Om), Sn)
+    torch.cuda.synchronize()
+    assert np.array_equal(S, Sn.cpu().numpy())
+    ctx.hss_compress(_dev(F), _dev(y), h, leaf, 1e-3, _dev(Om))
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    assert np.array_equal(perm, cluster_tree(F, leaf))
+    H = oracle_hss_from_export(exp, with_shift=False)
+    Kp = K[np.ix_(perm, perm)]
+    Kt = ohss.densify(H)
+    for a, b in zip(H.loff[:-1], H.loff[1:]):
+        assert np.abs(Kt[a:b, a:b] - Kp[a:b, a:b]).max() <= 1e-13
+    Ho = ohss.compress(F[perm], h, leaf, Om[perm], 1e-4, 1e-8, ctx.hss_stats()["rank_cap"])
+    err = np.linalg.norm(Kp - Kt) / np.linalg.norm(Kp)
+    err_o = np.linalg.norm(Kp - ohss.densify(Ho)) / np.linalg.norm(Kp)
+    assert err <= max(1.5 * err_o, 1e-3), (err, err_o)
+    est = ctx.hss_error_estimate(16, 1)
+    assert 0.3 * err <= est <= 3.0 * err + 1e-12
+    z = rng.random(n)
+    dec = ctx.svm_decision(_dev(G), _dev(z), -0.5).cpu().numpy()
+    dref = oadmm.decision(F, y, z, -0.5, G, h)
+    assert np.abs(dec - dref).max() <= 1e-10 * max(1.0, np.abs(dref).max())
+    # neighbour-based sampling searches on the values as given: lists identical to the oracle's
+    ctx2 = binding.Context()
+    ctx2.hss_set_i64("sampling", 1)
+    ctx2.hss_set_i64("ann_neighbours", 16)
+    ctx2.hss_set_i64("ann_trees", 1)
+    ctx2.hss_compress(_dev(F), _dev(y), h, leaf, 1e-2)
+    idx, dist = ctx2.hss_export_neighbours()
+    from oracle import ann as oann
+    from oracle.tree import leaf_offsets, tree_depth
+    L = tree_depth(n, leaf)
+    lc = L
+    while lc > 0 and (n >> lc) < 512:
+        lc -= 1
+    cells = leaf_offsets(n, lc)
+    ri, rd = oann.ann_projection_trees(F[perm], 16, int(np.diff(cells).max()), 1, first_cells=list(cells))
+    assert np.array_equal(idx, ri) and np.array_equal(dist, rd)
+    ctx2.close()
+    ctx.close()
