@@ -126,7 +126,8 @@ int hss_set_f64(hss_ctx* ctx, const char* key, double v);
 /* S = K(F,F) * Omega without forming K (the randomized range sampling the compression is built on,
  * end of Sec. 3.2).  F (dev, n x r), Omega (dev, n x s row-major), S_out (dev, n x s row-major), rows in
  * the order of F.  Stand-alone: needs no prior call and leaves the context's compressed matrix alone.
- * 1 <= r <= 96, s >= 1. */
+ * 1 <= r <= 384, s >= 1 (more than 112 features after padding to a multiple of 28: through row stripes of the kernel
+ * matrix in HBM instead of the fused kernel, see hss_compress). */
 int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h,
                       const double* Omega_dev, int32_t s, double* S_out_dev);
 
@@ -145,12 +146,15 @@ int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int3
 /* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection; option "clustering"),
  * sampling of the off-diagonal block rows (S = K Omega, or the neighbour-based sample; option "sampling"),
  * interpolative decompositions level by level.  F (dev, n x r), y (dev, n).  Any n >= 1; `leaf` = the largest leaf
- * size, a multiple of 16 with 16 <= leaf <= 1024; 1 <= r <= 96, h > 0, 0 < tol < 1.
+ * size, a multiple of 16 with 16 <= leaf <= 1024; 1 <= r <= 384, h > 0, 0 < tol < 1.
  * Shape of the tree: depth L = the smallest one with ceil(n / 2^L) <= leaf; a node of p points gives the lower
  * ceil(p/2) of them (in the order of its split) to the left child and the rest to the right one.  All leaves are on
  * level L and hold floor or ceil of n / 2^L points (n = leaf * 2^L: exactly `leaf` each).
  * The kernel products work on the points minus their feature means (the kernel of Sec. 1.1 sees differences only;
- * points far from the origin would otherwise lose digits in ||f_i||^2 + ||f_j||^2 - 2 f_i . f_j).  Pivots of each decomposition are kept while
+ * points far from the origin would otherwise lose digits in ||f_i||^2 + ||f_j||^2 - 2 f_i . f_j).
+ * Up to 112 features (after padding to a multiple of 28) the products with K run in the fused Gram + exp + contraction
+ * kernels and K is never stored; wider data goes through row stripes of K in HBM (batched GEMM for the Gram stripe,
+ * elementwise exp, batched GEMM with Omega; a work buffer of at most 8 GB), at about half the rate.  Pivots of each decomposition are kept while
  * |R_jj| > max(tol/10 * |R_00|, abs_tol), up to the rank cap.  Rank cap <= 512 and s <= 2048 (s <= 1024 for
  * tol < 3e-5), EUNSUPPORTED beyond.
  * Drops any previous compression and factorization held by the context.

@@ -28,6 +28,7 @@ namespace {
 
 constexpr double ANN_INF = __builtin_huge_val();   // +infinity
 constexpr int SEG_SHIFT = 40;
+constexpr int ANN_RMAX = 512;                      // most features (a point's row is staged in LDS per wavefront)
 
 struct PKey {          // projection-tree sort key
     double  v;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256) void knn_cell_kernel(const double* __restrict_
                                                        const int64_t* __restrict__ order,
                                                        const int64_t* __restrict__ celloff, int64_t ncells, int k,
                                                        int32_t* __restrict__ nbr_idx, double* __restrict__ nbr_dist) {
-    __shared__ double xs[4][128];
+    __shared__ double xs[4][ANN_RMAX];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int64_t pos = (int64_t)blockIdx.x * 4 + wave;
     const bool live = pos < n;
@@ -285,7 +286,7 @@ int ann_search(hss_ctx* c, const double* F, int k, int cell, int trees, uint64_t
     const int64_t n = c->n;
     const int r = c->r;
     const int64_t* perm = c->perm.as<int64_t>();
-    if (k < 1 || k > 64 || trees < 1 || cell < 2 || n >= (int64_t(1) << 31)) return HSS_EINVAL;
+    if (k < 1 || k > 64 || trees < 1 || cell < 2 || n >= (int64_t(1) << 31) || r > ANN_RMAX) return HSS_EINVAL;
     // cells: the nodes of the deepest level of the cluster tree whose nodes all hold at least `cell` points (the
     // root if none does); every projection tree is split down to the same level
     int lc = c->L;

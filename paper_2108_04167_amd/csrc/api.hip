@@ -76,7 +76,7 @@ int hss_set_f64(hss_ctx* c, const char* key, double v) {
 int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, double h, const double* Omega_dev,
                       int32_t s, double* S_out_dev) {
     if (!ctx || !F_dev || !Omega_dev || !S_out_dev || n < 1 || r < 1 || s < 1 || !(h > 0.0)) return HSS_EINVAL;
-    if (r > 96) return HSS_EUNSUPPORTED;
+    if (r > MAX_FEATURES) return HSS_EUNSUPPORTED;
     hipStream_t st = ctx->stream;
     const int64_t n_pad = round_up(n, 256);
     const int r_pad = feature_pad(r), s_pad = (int)round_up(s, 128);
@@ -92,7 +92,8 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
     HSS_TRY(column_means_launch(st, Fp.as<double>(), n, r, r_pad, S.as<double>(), mean.as<double>()));
     HSS_TRY(centre_rows_launch(st, Fp.as<double>(), n, r, r_pad, mean.as<double>()));
     HSS_TRY(row_norms_launch(st, Fp.as<double>(), nu.as<double>(), n_pad, r_pad));
-    HSS_TRY(sample_launch(st, Fp.as<double>(), nu.as<double>(), Om.as<double>(), S.as<double>(), n_pad, r_pad, s_pad, h));
+    HSS_TRY(kernel_product_launch(st, Fp.as<double>(), nu.as<double>(), n_pad, Fp.as<double>(), nu.as<double>(), n_pad,
+                                  Om.as<double>(), S.as<double>(), r_pad, s_pad, s_pad, h));
     HIP_TRY(hipMemcpy2DAsync(S_out_dev, sizeof(double) * s, S.p, sizeof(double) * s_pad, sizeof(double) * s, n,
                              hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));   // the temporaries are freed on return
@@ -133,8 +134,8 @@ int hss_error_estimate(hss_ctx* c, int32_t nprobe, uint64_t seed, double* rel_er
         HSS_TRY(sample_narrow_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(), c->nu.as<double>(),
                                      n_pad, Z.as<double>(), KZ.as<double>(), c->r_pad, c->h, work));
     else
-        HSS_TRY(sample_launch(st, c->Fp.as<double>(), c->nu.as<double>(), Z.as<double>(), KZ.as<double>(), n_pad, c->r_pad,
-                              sp, c->h));
+        HSS_TRY(kernel_product_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(),
+                                      c->nu.as<double>(), n_pad, Z.as<double>(), KZ.as<double>(), c->r_pad, sp, sp, c->h));
     double* part = c->partial.as<double>();
     double* scal = c->scal.as<double>();
     double num = 0.0, den = 0.0;

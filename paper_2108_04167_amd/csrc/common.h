@@ -164,6 +164,15 @@ int sample_launch_rect(hipStream_t st, const double* Fr, const double* nur, int6
 int sample_launch_window(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
                          const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
                          double h);
+// The same product for any padded feature count: the fused kernel up to 112 features, row stripes of the kernel matrix
+// in HBM beyond (sample_wide.hip; allocates its stripe and drains the stream)
+int sample_wide_launch(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                       const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
+                       double h);
+int kernel_product_launch(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
+                          const double* nu, int64_t n_pad, const double* Om, double* S, int r_pad, int width, int ld,
+                          double h);
+constexpr int MAX_FEATURES = 384;        // r accepted by the compression (padded to 392)
 // S (nr_pad x 16) = K(rows, cols) V for a block V (n_pad x 16) of at most 16 used columns (sample_narrow.hip); `work`
 // is grown to hold partial results when the rows are few
 int sample_narrow_launch(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,

@@ -255,7 +255,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     if (!c || !F || !y) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol < 1.0)) return HSS_EINVAL;
     if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
-    if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
+    if (r > MAX_FEATURES || leaf > 1024) return HSS_EUNSUPPORTED;
     const int L = tree_depth(n, leaf);                       // any n: leaves of ceil or floor of n / 2^L points
     if (L > 24) return HSS_EUNSUPPORTED;
     const int64_t nl = int64_t(1) << L;
@@ -364,9 +364,9 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
     auto sample_columns = [&](int c0, int c1) -> int {
         const int w = (int)round_up(c1 - c0, 128);
         if (hipEventRecord(ev0, st) != hipSuccess) return HSS_EHIP;
-        int src = sample_launch_window(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(),
-                                       c->nu.as<double>(), n_pad, Ob[0].as<double>() + c0, Sb[0].as<double>() + c0, r_pad, w,
-                                       LD, h);
+        int src = kernel_product_launch(st, c->Fp.as<double>(), c->nu.as<double>(), n_pad, c->Fp.as<double>(),
+                                        c->nu.as<double>(), n_pad, Ob[0].as<double>() + c0, Sb[0].as<double>() + c0, r_pad, w,
+                                        LD, h);
         (void)hipEventRecord(ev1, st);
         hipError_t serr = hipStreamSynchronize(st);
         float ms = 0.f;
@@ -648,7 +648,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
     if (!c || !F || !y || !perm_h || !sizes || !ranks || !D || !U || !J || !B) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(delta >= 0.0) || !(delta <= 1.7976931348623157e308)) return HSS_EINVAL;
     if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
-    if (r > 96 || leaf > 1024) return HSS_EUNSUPPORTED;
+    if (r > MAX_FEATURES || leaf > 1024) return HSS_EUNSUPPORTED;
     const int L = tree_depth(n, leaf);
     if (L > 24) return HSS_EUNSUPPORTED;
     const int64_t nl = int64_t(1) << L;

@@ -9,39 +9,44 @@
 namespace {
 
 // out[i][j] = exp(-||f_ri - f_cj||^2 / (2 h^2)) by direct differences (kernel definition, Sec. 1.1).
-// 16 x 16 outputs per workgroup; the 32 points involved are staged in LDS.
+// 16 x 16 outputs per workgroup; the 32 points involved are staged in LDS, KB_CHUNK features at a time (the squared
+// distance is accumulated feature by feature in index order whatever the chunking).
+constexpr int KB_CHUNK = 112;
 __global__ __launch_bounds__(256) void kernel_block_kernel(const KBItem* __restrict__ items, const double* __restrict__ Fp,
                                                            int r_pad, int tilesC, double inv2h2) {
     const KBItem it = items[blockIdx.x];
     const int tr = blockIdx.y / tilesC, tc = blockIdx.y % tilesC;
     const int i0 = tr * 16, j0 = tc * 16;
     if (i0 >= it.nr || j0 >= it.nc) return;
-    extern __shared__ double sm[];
-    const int ldf = r_pad + 1;
-    double* Fr = sm;              // 16 x ldf
-    double* Fc = sm + 16 * ldf;   // 16 x ldf
+    constexpr int ldf = KB_CHUNK + 1;
+    __shared__ double Fr[16 * ldf];
+    __shared__ double Fc[16 * ldf];
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < 16 * r_pad; idx += 256) {
-        int q = idx / r_pad, f = idx - q * r_pad;
-        int i = i0 + q, j = j0 + q;
-        double a = 0.0, b = 0.0;
-        if (i < it.nr) {
-            int64_t g = it.ridx ? it.ridx[i] : it.r0 + i;
-            a = Fp[g * r_pad + f];
-        }
-        if (j < it.nc) {
-            int64_t g = it.cidx ? it.cidx[j] : it.c0 + j;
-            b = Fp[g * r_pad + f];
-        }
-        Fr[q * ldf + f] = a;
-        Fc[q * ldf + f] = b;
-    }
-    __syncthreads();
     const int li = tid >> 4, lj = tid & 15;
     double d2 = 0.0;
-    for (int f = 0; f < r_pad; ++f) {
-        double d = Fr[li * ldf + f] - Fc[lj * ldf + f];
-        d2 += d * d;
+    for (int f0 = 0; f0 < r_pad; f0 += KB_CHUNK) {
+        const int fw = r_pad - f0 < KB_CHUNK ? r_pad - f0 : KB_CHUNK;
+        for (int idx = tid; idx < 16 * fw; idx += 256) {
+            int q = idx / fw, f = idx - q * fw;
+            int i = i0 + q, j = j0 + q;
+            double a = 0.0, b = 0.0;
+            if (i < it.nr) {
+                int64_t g = it.ridx ? it.ridx[i] : it.r0 + i;
+                a = Fp[g * r_pad + f0 + f];
+            }
+            if (j < it.nc) {
+                int64_t g = it.cidx ? it.cidx[j] : it.c0 + j;
+                b = Fp[g * r_pad + f0 + f];
+            }
+            Fr[q * ldf + f] = a;
+            Fc[q * ldf + f] = b;
+        }
+        __syncthreads();
+        for (int f = 0; f < fw; ++f) {
+            double d = Fr[li * ldf + f] - Fc[lj * ldf + f];
+            d2 += d * d;
+        }
+        __syncthreads();
     }
     const int i = i0 + li, j = j0 + lj;
     if (i < it.nr && j < it.nc) it.out[(size_t)i * it.ldo + j] = exp(-d2 * inv2h2);
@@ -124,8 +129,7 @@ int kernel_blocks(hipStream_t st, DescArena& ar, const std::vector<KBItem>& item
     if ((int64_t)tilesR * tilesC > 65535) return HSS_EUNSUPPORTED;
     const KBItem* d = (const KBItem*)ar.push(items.data(), sizeof(KBItem) * items.size(), st);
     if (!d) return HSS_ENOMEM;
-    size_t smem = sizeof(double) * 32 * (r_pad + 1);
-    hipLaunchKernelGGL(kernel_block_kernel, dim3((unsigned)items.size(), (unsigned)(tilesR * tilesC)), dim3(256), smem, st,
+    hipLaunchKernelGGL(kernel_block_kernel, dim3((unsigned)items.size(), (unsigned)(tilesR * tilesC)), dim3(256), 0, st,
                        d, Fp, r_pad, tilesC, 1.0 / (2.0 * h * h));
     HIP_TRY(hipGetLastError());
     return HSS_OK;

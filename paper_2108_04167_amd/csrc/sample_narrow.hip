@@ -173,10 +173,12 @@ int narrow_go(hipStream_t st, const double* Fr, const double* nur, int nr_pad, c
 }  // namespace
 
 // S (nr_pad x 16) = K(rows, cols) V with rows = the points (Fr, nur), cols = the points (Fp, nu); V is n_pad x 16
-// (unused columns zero).  Both point sets are padded (rows to a multiple of 256, features to r_pad, a multiple of 28
-// up to 112).  `work` is grown to hold the partial results of the column splits.
+// (unused columns zero).  Both point sets are padded (rows to a multiple of 256, features to r_pad, a multiple of
+// 28; above 112 the product goes through sample_wide_launch).  `work` is grown to hold the partial results of the
+// column splits.
 int sample_narrow_launch(hipStream_t st, const double* Fr, const double* nur, int64_t nr_pad, const double* Fp,
                          const double* nu, int64_t n_pad, const double* V, double* S, int r_pad, double h, DevBuf& work) {
+    if (r_pad > 112) return sample_wide_launch(st, Fr, nur, nr_pad, Fp, nu, n_pad, V, S, r_pad, 16, 16, h);
     if (n_pad % 256 || nr_pad % 256 || n_pad < 256 || nr_pad < 256 || r_pad % 28 || r_pad < 28 || r_pad > 112 ||
         nr_pad >= (int64_t(1) << 31) || n_pad >= (int64_t(1) << 31))
         return HSS_EUNSUPPORTED;

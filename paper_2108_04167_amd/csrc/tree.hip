@@ -19,6 +19,7 @@ namespace {
 
 constexpr int TREE_CHUNK = 256;   // points per partial sum
 constexpr int SEG_SHIFT = 40;     // key word = (node << 40) | original index
+constexpr int TREE_RMAX = 512;    // most coordinates (one thread each in the per-node kernels)
 
 struct TreeKey {
     double  v;
@@ -40,7 +41,8 @@ __global__ __launch_bounds__(256) void tree_iota_kernel(int64_t* idx, int64_t n)
 }
 
 // partial[block][c] = sum over the block's chunk of points of F[idx][c] (MODE 0) or of
-// (F[idx][c] - mean[node][c])^2 (MODE 1).  Thread t works on coordinate t % r of every (256 / r)-th point.
+// (F[idx][c] - mean[node][c])^2 (MODE 1).  The coordinates are taken in groups of at most 256; within a group of rc
+// coordinates thread t works on coordinate t % rc of every (256 / rc)-th point.
 template <int MODE>
 __global__ __launch_bounds__(256) void tree_partial_kernel(const double* __restrict__ F, int r,
                                                            const int64_t* __restrict__ idx,
@@ -48,30 +50,34 @@ __global__ __launch_bounds__(256) void tree_partial_kernel(const double* __restr
                                                            const double* __restrict__ mean, double* __restrict__ partial) {
     const int64_t node = blockIdx.x / chunks;
     const int ch = blockIdx.x % chunks;
-    const int npl = 256 / r;
-    const int c = threadIdx.x % r, pl = threadIdx.x / r;
     __shared__ double red[256];
-    double acc = 0.0;
     const int64_t lo = noff[node] + (int64_t)ch * TREE_CHUNK, end = noff[node + 1];   // lo >= end: an empty chunk
     const int64_t hi = lo + TREE_CHUNK < end ? lo + TREE_CHUNK : end;
-    if (pl < npl) {
-        const double m = MODE ? mean[node * r + c] : 0.0;
-        for (int64_t i = lo + pl; i < hi; i += npl) {
-            const double d = F[idx[i] * r + c] - m;
-            acc += MODE ? d * d : d;
+    for (int c0 = 0; c0 < r; c0 += 256) {
+        const int rc = r - c0 < 256 ? r - c0 : 256;
+        const int npl = 256 / rc;
+        const int c = c0 + threadIdx.x % rc, pl = threadIdx.x / rc;
+        double acc = 0.0;
+        if (pl < npl) {
+            const double m = MODE ? mean[node * r + c] : 0.0;
+            for (int64_t i = lo + pl; i < hi; i += npl) {
+                const double d = F[idx[i] * r + c] - m;
+                acc += MODE ? d * d : d;
+            }
         }
-    }
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    if (threadIdx.x < r) {
-        double s = 0.0;
-        for (int p = 0; p < npl; ++p) s += red[p * r + threadIdx.x];
-        partial[(size_t)blockIdx.x * r + threadIdx.x] = s;
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        if (threadIdx.x < rc) {
+            double s = 0.0;
+            for (int p = 0; p < npl; ++p) s += red[p * rc + threadIdx.x];
+            partial[(size_t)blockIdx.x * r + c0 + threadIdx.x] = s;
+        }
+        __syncthreads();
     }
 }
 
 // mean[node][c] = (sum of the node's partials, in chunk order) / (points of the node)
-__global__ __launch_bounds__(128) void tree_mean_kernel(const double* __restrict__ partial, int r, int chunks,
+__global__ __launch_bounds__(TREE_RMAX) void tree_mean_kernel(const double* __restrict__ partial, int r, int chunks,
                                                         const int64_t* __restrict__ noff, double* __restrict__ mean) {
     const int c = threadIdx.x;
     if (c >= r) return;
@@ -84,9 +90,9 @@ __global__ __launch_bounds__(128) void tree_mean_kernel(const double* __restrict
 // best[node] = lowest coordinate whose summed squared deviation reaches (1 - 1e-9) x the largest.  A sum that is
 // not finite (a NaN or an infinity among the features, or squares that overflow) sets *bad: at the root this
 // covers every entry of F.
-__global__ __launch_bounds__(128) void tree_best_kernel(const double* __restrict__ partial, int r, int chunks,
+__global__ __launch_bounds__(TREE_RMAX) void tree_best_kernel(const double* __restrict__ partial, int r, int chunks,
                                                         int* __restrict__ best, int* __restrict__ bad) {
-    __shared__ double var[128];
+    __shared__ double var[TREE_RMAX];
     const int c = threadIdx.x;
     if (c < r) {
         const double* p = partial + (size_t)blockIdx.x * chunks * r + c;
@@ -164,58 +170,65 @@ __global__ __launch_bounds__(256) void tm_amax_kernel(const double* __restrict__
 }
 
 // qsum[(node*2 + side)*r + c] += sum of rint(F * scale) over the chunk's points on that side; cnt[node*2 + side]
-// += their number.  side == nullptr: every point counts as side 0.
+// += their number.  side == nullptr: every point counts as side 0.  Coordinates in groups of at most 256, as in
+// tree_partial_kernel; the integer sums are exact, so the grouping does not show in the result.
 __global__ __launch_bounds__(256) void tm_sum_kernel(const double* __restrict__ F, int r, const int64_t* __restrict__ idx,
                                                      const int64_t* __restrict__ noff, int chunks, double scale,
                                                      const unsigned char* __restrict__ side, u64* __restrict__ qsum,
                                                      u64* __restrict__ cnt) {
     const int64_t node = blockIdx.x / chunks;
     const int ch = blockIdx.x % chunks;
-    const int npl = 256 / r;
-    const int c = threadIdx.x % r, pl = threadIdx.x / r;
     __shared__ long long red[2][256];
-    long long acc0 = 0, acc1 = 0, n0 = 0, n1 = 0;
     const int64_t lo = noff[node] + (int64_t)ch * TREE_CHUNK, end = noff[node + 1];   // lo >= end: an empty chunk
     const int64_t hi = lo + TREE_CHUNK < end ? lo + TREE_CHUNK : end;
-    if (pl < npl) {
-        for (int64_t i = lo + pl; i < hi; i += npl) {
-            const long long q = (long long)rint(F[idx[i] * r + c] * scale);
-            const int sd = side ? side[i] : 0;
-            if (sd) { acc1 += q; ++n1; }
-            else { acc0 += q; ++n0; }
+    for (int c0 = 0; c0 < r; c0 += 256) {
+        const int rc = r - c0 < 256 ? r - c0 : 256;
+        const int npl = 256 / rc;
+        const int c = c0 + threadIdx.x % rc, pl = threadIdx.x / rc;
+        long long acc0 = 0, acc1 = 0, n0 = 0, n1 = 0;
+        if (pl < npl) {
+            for (int64_t i = lo + pl; i < hi; i += npl) {
+                const long long q = (long long)rint(F[idx[i] * r + c] * scale);
+                const int sd = side ? side[i] : 0;
+                if (sd) { acc1 += q; ++n1; }
+                else { acc0 += q; ++n0; }
+            }
         }
-    }
-    red[0][threadIdx.x] = acc0;
-    red[1][threadIdx.x] = acc1;
-    __syncthreads();
-    if (threadIdx.x < r) {
-        long long s0 = 0, s1 = 0;
-        for (int p = 0; p < npl; ++p) {
-            s0 += red[0][p * r + threadIdx.x];
-            s1 += red[1][p * r + threadIdx.x];
+        red[0][threadIdx.x] = acc0;
+        red[1][threadIdx.x] = acc1;
+        __syncthreads();
+        if (threadIdx.x < rc) {
+            long long s0 = 0, s1 = 0;
+            for (int p = 0; p < npl; ++p) {
+                s0 += red[0][p * rc + threadIdx.x];
+                s1 += red[1][p * rc + threadIdx.x];
+            }
+            atomicAdd(qsum + (size_t)(node * 2) * r + c0 + threadIdx.x, (u64)s0);
+            atomicAdd(qsum + (size_t)(node * 2 + 1) * r + c0 + threadIdx.x, (u64)s1);
         }
-        atomicAdd(qsum + (size_t)(node * 2) * r + threadIdx.x, (u64)s0);
-        atomicAdd(qsum + (size_t)(node * 2 + 1) * r + threadIdx.x, (u64)s1);
-    }
-    __syncthreads();
-    // the number of points per side: coordinate 0's threads saw every point of the chunk once
-    red[0][threadIdx.x] = (c == 0 && pl < npl) ? n0 : 0;
-    red[1][threadIdx.x] = (c == 0 && pl < npl) ? n1 : 0;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        long long s0 = 0, s1 = 0;
-        for (int p = 0; p < npl; ++p) {
-            s0 += red[0][p * r];
-            s1 += red[1][p * r];
+        __syncthreads();
+        if (c0 == 0) {
+            // the number of points per side: coordinate 0's threads saw every point of the chunk once
+            red[0][threadIdx.x] = (c == 0 && pl < npl) ? n0 : 0;
+            red[1][threadIdx.x] = (c == 0 && pl < npl) ? n1 : 0;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                long long s0 = 0, s1 = 0;
+                for (int p = 0; p < npl; ++p) {
+                    s0 += red[0][p * rc];
+                    s1 += red[1][p * rc];
+                }
+                atomicAdd(cnt + node * 2, (u64)s0);
+                atomicAdd(cnt + node * 2 + 1, (u64)s1);
+            }
+            __syncthreads();
         }
-        atomicAdd(cnt + node * 2, (u64)s0);
-        atomicAdd(cnt + node * 2 + 1, (u64)s1);
     }
 }
 
 // ctr[(node*2 + side)*r + c] = ((double)sum / (double)count) / scale.  both == 0: side 0 only (the node's mean);
 // both == 1: both sides, and only when neither is empty (an empty side leaves the centres as they are).
-__global__ __launch_bounds__(128) void tm_centre_kernel(const u64* __restrict__ qsum, const u64* __restrict__ cnt, int r,
+__global__ __launch_bounds__(TREE_RMAX) void tm_centre_kernel(const u64* __restrict__ qsum, const u64* __restrict__ cnt, int r,
                                                         double scale, int both, double* __restrict__ ctr) {
     const int64_t node = blockIdx.x;
     const int c = threadIdx.x;
@@ -249,7 +262,7 @@ __global__ __launch_bounds__(256) void tm_far2_kernel(const int64_t* __restrict_
     if ((u64)__double_as_longlong(d2[i]) == dmax[node]) atomicMin(amin + node, (u64)idx[i]);
 }
 // centre `which` of every node = the point amin[node]
-__global__ __launch_bounds__(128) void tm_take_point_kernel(const double* __restrict__ F, int r, const u64* __restrict__ amin,
+__global__ __launch_bounds__(TREE_RMAX) void tm_take_point_kernel(const double* __restrict__ F, int r, const u64* __restrict__ amin,
                                                             int which, double* __restrict__ ctr) {
     const int64_t node = blockIdx.x;
     const int c = threadIdx.x;
@@ -312,7 +325,7 @@ int upload_level_offsets(hipStream_t st, int64_t n, int L, LevelOffsets& lo) {
 
 int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int iters,
                               int64_t* perm_dev, int* bad_dev) {
-    if (r < 1 || r > 128 || n < 1 || n >= (int64_t(1) << 24) || iters < 0) return HSS_EINVAL;
+    if (r < 1 || r > TREE_RMAX || n < 1 || n >= (int64_t(1) << 24) || iters < 0) return HSS_EINVAL;
     const unsigned nb = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(tree_iota_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n);
     HIP_TRY(hipGetLastError());
@@ -364,7 +377,7 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
             HIP_TRY(hipMemsetAsync(cnt.p, 0, sizeof(u64) * (size_t)nodes * 2, st));
             hipLaunchKernelGGL(tm_sum_kernel, dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks, scale, sd,
                                qsum.as<u64>(), cnt.as<u64>());
-            hipLaunchKernelGGL(tm_centre_kernel, dim3((unsigned)nodes), dim3(128), 0, st, qsum.as<u64>(), cnt.as<u64>(), r,
+            hipLaunchKernelGGL(tm_centre_kernel, dim3((unsigned)nodes), dim3(TREE_RMAX), 0, st, qsum.as<u64>(), cnt.as<u64>(), r,
                                scale, both, ctr.as<double>());
             HIP_TRY(hipGetLastError());
             return HSS_OK;
@@ -376,7 +389,7 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
                                ctr.as<double>(), d2.as<double>(), dmax.as<u64>());
             hipLaunchKernelGGL(tm_far2_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n, noff, nodes, d2.as<double>(),
                                dmax.as<u64>(), amin.as<u64>());
-            hipLaunchKernelGGL(tm_take_point_kernel, dim3((unsigned)nodes), dim3(128), 0, st, F_dev, r, amin.as<u64>(), which,
+            hipLaunchKernelGGL(tm_take_point_kernel, dim3((unsigned)nodes), dim3(TREE_RMAX), 0, st, F_dev, r, amin.as<u64>(), which,
                                ctr.as<double>());
             HIP_TRY(hipGetLastError());
             return HSS_OK;
@@ -403,7 +416,7 @@ int build_cluster_tree_2means(hipStream_t st, const double* F_dev, int64_t n, in
 // perm_dev[i] = original index of the i-th point in leaf order.  F_dev is n x r row-major; any n >= 1.
 // *bad_dev (an int the caller zeroed) is set when F holds a value that is not finite.
 int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, int leaf, int64_t* perm_dev, int* bad_dev) {
-    if (r < 1 || r > 128 || n < 1 || n >= (int64_t(1) << SEG_SHIFT)) return HSS_EINVAL;
+    if (r < 1 || r > TREE_RMAX || n < 1 || n >= (int64_t(1) << SEG_SHIFT)) return HSS_EINVAL;
     const unsigned nb = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(tree_iota_kernel, dim3(nb), dim3(256), 0, st, perm_dev, n);
     HIP_TRY(hipGetLastError());
@@ -430,11 +443,11 @@ int build_cluster_tree(hipStream_t st, const double* F_dev, int64_t n, int r, in
         const int64_t* noff = lo.level(l);
         hipLaunchKernelGGL((tree_partial_kernel<0>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks,
                            (const double*)nullptr, partial.as<double>());
-        hipLaunchKernelGGL(tree_mean_kernel, dim3((unsigned)nodes), dim3(128), 0, st, partial.as<double>(), r, chunks,
+        hipLaunchKernelGGL(tree_mean_kernel, dim3((unsigned)nodes), dim3(TREE_RMAX), 0, st, partial.as<double>(), r, chunks,
                            noff, mean.as<double>());
         hipLaunchKernelGGL((tree_partial_kernel<1>), dim3(grid), dim3(256), 0, st, F_dev, r, perm_dev, noff, chunks,
                            mean.as<double>(), partial.as<double>());
-        hipLaunchKernelGGL(tree_best_kernel, dim3((unsigned)nodes), dim3(128), 0, st, partial.as<double>(), r, chunks,
+        hipLaunchKernelGGL(tree_best_kernel, dim3((unsigned)nodes), dim3(TREE_RMAX), 0, st, partial.as<double>(), r, chunks,
                            best.as<int>(), bad_dev);
         hipLaunchKernelGGL(tree_keys_kernel, dim3(nb), dim3(256), 0, st, F_dev, r, perm_dev, n, noff, nodes,
                            best.as<int>(), keys_a.as<TreeKey>());

@@ -43,7 +43,7 @@ int stream_copy_launch(hipStream_t st, const double* src, double* dst, int64_t n
 // as many digits as the norms exceed the distances by: data with an offset would lose them all).
 constexpr int CENTRE_ROWS = 1024;            // rows per partial sum
 inline int64_t centre_work_doubles(int64_t n, int r) { return (n + CENTRE_ROWS - 1) / CENTRE_ROWS * r; }
-// mean[c] = (sum over the first n rows of X[row * ld + c]) / n for c < r <= 256, partial sums of 1024 rows added in a
+// mean[c] = (sum over the first n rows of X[row * ld + c]) / n for c < r, partial sums of 1024 rows added in a
 // fixed order; work: centre_work_doubles(n, r) doubles
 int column_means_launch(hipStream_t st, const double* X, int64_t n, int r, int ld, double* work, double* mean);
 // X[row * ld + c] -= mean[c] for row < n, c < r

@@ -225,33 +225,38 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const double2* __restr
 }  // namespace
 
 namespace {
-// partial[b * r + c] = sum over rows b*CENTRE_ROWS .. of X[row * ld + c]; thread t adds column t % r of every
-// (256 / r)-th row, then the 256 / r partial sums of a column are added in order
+// partial[b * r + c] = sum over rows b*CENTRE_ROWS .. of X[row * ld + c]; columns in groups of at most 256; within a
+// group of rc columns thread t adds column t % rc of every (256 / rc)-th row, then the partial sums of a column
+// are added in order
 __global__ __launch_bounds__(256) void col_partial_kernel(const double* __restrict__ X, int64_t n, int r, int ld,
                                                           double* __restrict__ partial) {
-    const int npl = 256 / r;
-    const int c = threadIdx.x % r, pl = threadIdx.x / r;
     __shared__ double red[256];
     const int64_t lo = (int64_t)blockIdx.x * CENTRE_ROWS;
     const int64_t hi = lo + CENTRE_ROWS < n ? lo + CENTRE_ROWS : n;
-    double acc = 0.0;
-    if (pl < npl)
-        for (int64_t i = lo + pl; i < hi; i += npl) acc += X[i * ld + c];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    if (threadIdx.x < r) {
-        double s = 0.0;
-        for (int p = 0; p < npl; ++p) s += red[p * r + threadIdx.x];
-        partial[(size_t)blockIdx.x * r + threadIdx.x] = s;
+    for (int c0 = 0; c0 < r; c0 += 256) {
+        const int rc = r - c0 < 256 ? r - c0 : 256;
+        const int npl = 256 / rc;
+        const int c = c0 + threadIdx.x % rc, pl = threadIdx.x / rc;
+        double acc = 0.0;
+        if (pl < npl)
+            for (int64_t i = lo + pl; i < hi; i += npl) acc += X[i * ld + c];
+        red[threadIdx.x] = acc;
+        __syncthreads();
+        if (threadIdx.x < rc) {
+            double s = 0.0;
+            for (int p = 0; p < npl; ++p) s += red[p * rc + threadIdx.x];
+            partial[(size_t)blockIdx.x * r + c0 + threadIdx.x] = s;
+        }
+        __syncthreads();
     }
 }
 __global__ __launch_bounds__(256) void col_mean_kernel(const double* __restrict__ partial, int64_t chunks, int r, double n,
                                                        double* __restrict__ mean) {
-    const int c = threadIdx.x;
-    if (c >= r) return;
-    double s = 0.0;
-    for (int64_t b = 0; b < chunks; ++b) s += partial[b * r + c];
-    mean[c] = s / n;
+    for (int c = threadIdx.x; c < r; c += 256) {
+        double s = 0.0;
+        for (int64_t b = 0; b < chunks; ++b) s += partial[b * r + c];
+        mean[c] = s / n;
+    }
 }
 __global__ __launch_bounds__(256) void centre_rows_kernel(double* __restrict__ X, int64_t n, int r, int ld,
                                                           const double* __restrict__ mean) {
@@ -365,7 +370,7 @@ int decision_finish(hipStream_t st, double* dec, const double* S, int ld, double
     return HSS_OK;
 }
 int column_means_launch(hipStream_t st, const double* X, int64_t n, int r, int ld, double* work, double* mean) {
-    if (n < 1 || r < 1 || r > 256) return HSS_EINVAL;
+    if (n < 1 || r < 1) return HSS_EINVAL;
     const int64_t chunks = (n + CENTRE_ROWS - 1) / CENTRE_ROWS;
     hipLaunchKernelGGL(col_partial_kernel, dim3((unsigned)chunks), dim3(256), 0, st, X, n, r, ld, work);
     hipLaunchKernelGGL(col_mean_kernel, dim3(1), dim3(256), 0, st, work, chunks, r, (double)n, mean);

@@ -107,7 +107,7 @@ def test_limits_are_rejected_not_run():
     w = synth.make_workload(1, n=2048, leaf=64, s=128)
     ctx = binding.Context()
     y = _dev(w.y)
-    wide = _dev(np.zeros((2048, 97)))
+    wide = _dev(np.zeros((2048, 385)))
     with pytest.raises(binding.HssError) as e:
         ctx.hss_compress(wide, y, 1.0, 64, 1e-3)
     assert e.value.code == binding.HSS_EUNSUPPORTED
