@@ -1,0 +1,77 @@
+"""One context used for a sequence of different problems (GPU only): sizes up and down, few and many features,
+random and neighbour-based sampling, both trees, a factorization and an ADMM run in between.  Every step must give
+bit for bit what a fresh context gives for the same problem: nothing of an earlier, larger problem may leak into a
+later one (the context's buffers only grow)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2108_04167_amd import binding   # noqa: E402
+
+
+def _dev(a):
+    import torch
+    return torch.tensor(np.ascontiguousarray(a), device="cuda:0")
+
+
+def _problem(n, r, seed):
+    g = np.random.default_rng(seed)
+    F = g.standard_normal((n, r)) * (0.3 if r > 20 else 1.0)
+    F[:, 0] += 0.5 * g.standard_normal(n)
+    y = np.where(g.random(n) < 0.5, 1.0, -1.0)
+    G = g.standard_normal((37, r))
+    return F, y, G
+
+
+def _run(ctx, F, y, G, h, leaf, s, opts, beta, C, its):
+    """Set every option the sequence touches (so that a reused context carries none over), then the whole path."""
+    full = dict(sampling=0, clustering=0, adaptive_start=0, max_rank=0, ann_neighbours=64, ann_trees=3, seed=0)
+    full.update(opts)
+    ctx.hss_set_i64("sample_width", s)
+    for k, v in full.items():
+        ctx.hss_set_i64(k, v)
+    rc = ctx.hss_compress(_dev(F), _dev(y), h, leaf, 1e-3)
+    exp = ctx.hss_export()
+    out = ctx.admm_svm_train(C, beta, its)
+    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
+    est = ctx.hss_error_estimate(4, 9)
+    st = ctx.hss_stats()
+    return dict(rc=rc, perm=exp["perm"], sizes=exp["sizes"], ranks=exp["ranks"], U=exp["U"], B=exp["B"], J=exp["J"],
+                D=np.concatenate([np.asarray(d).reshape(-1) for d in exp["D"]]), delta=exp["delta"],
+                x=out["x"].cpu().numpy(), z=out["z"].cpu().numpy(), mu=out["mu"].cpu().numpy(), bias=out["bias"],
+                dec=dec, est=est, cap=st["rank_cap"], width=st["sample_width_used"])
+
+
+SEQUENCE = [
+    # n, r, h, leaf, s, options, beta, C, iterations
+    (1000, 8, 1.5, 64, 128, {}, 1.0, 1.0, 12),
+    (3001, 54, 3.0, 256, 512, {}, 0.5, 10.0, 8),
+    (500, 3, 0.8, 32, 128, {"sampling": 1, "ann_neighbours": 16}, 1.0, 1.0, 10),
+    (2048, 123, 2.0, 64, 128, {"clustering": 1}, 2.0, 1.0, 6),
+    (777, 22, 2.0, 128, 256, {"adaptive_start": 128}, 1.0, 0.1, 9),
+    (64, 5, 1.0, 64, 128, {}, 1.0, 1.0, 5),                              # a single leaf
+    (4099, 18, 1.0, 256, 512, {"sampling": 1, "clustering": 1}, 1.0, 10.0, 6),
+    (1000, 8, 1.5, 64, 128, {}, 1.0, 1.0, 12),                           # the first problem again
+]
+
+
+def test_one_context_for_many_problems():
+    shared = binding.Context()
+    first = None
+    for step, (n, r, h, leaf, s, opts, beta, C, its) in enumerate(SEQUENCE):
+        F, y, G = _problem(n, r, 100 + step if step != len(SEQUENCE) - 1 else 100)
+        got = _run(shared, F, y, G, h, leaf, s, opts, beta, C, its)
+        fresh = binding.Context()
+        ref = _run(fresh, F, y, G, h, leaf, s, opts, beta, C, its)
+        fresh.close()
+        for key in ref:
+            a, b = got[key], ref[key]
+            same = np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b
+            assert same, (step, key)
+        if step == 0:
+            first = got
+    for key in first:                      # and the last step repeated the first problem
+        a, b = got[key], first[key]
+        assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, key
+    shared.close()
