@@ -68,8 +68,39 @@ def _bgemm(L, shapes, ta, tb, alpha, beta, seed=0):
 def test_batched_gemm(L, ta, tb):
     shapes = [(64, 64, 16), (1, 1, 1), (70, 33, 5), (129, 200, 77), (16, 300, 130), (300, 17, 64), (5, 5, 0),
               (100, 100, 100), (502, 512, 1004)]
-    assert _bgemm(L, shapes, ta, tb, 1.0, 0.0) < 1e-13
+    assert _bgemm(L, shapes, ta, tb, 1.0, 0.0) < 1e-13            # items of 128 x 128 and more: the 128 x 128-tile kernel
     assert _bgemm(L, shapes, ta, tb, -0.5, 1.0, seed=1) < 1e-13
+    small = [(64, 64, 16), (1, 1, 1), (70, 33, 5), (100, 127, 77), (127, 100, 130), (16, 127, 300), (5, 5, 0)]
+    assert _bgemm(L, small, ta, tb, 1.0, 0.0, seed=2) < 1e-13       # the 64 x 64-tile kernel
+    assert _bgemm(L, small, ta, tb, 2.0, -1.0, seed=3) < 1e-13
+
+
+def test_gemm_tile_sizes_give_the_same_bits(L):
+    """One 200 x 200 x 77 product as a single item (the 128 x 128-tile kernel) and as four 100 x 100 quadrants (the
+    64 x 64-tile kernel) of the same operands: every output element adds its k-steps in the same order."""
+    from gpu_helpers import dev, hptr, ptr
+    rng = np.random.default_rng(9)
+    M = N = 200
+    K = 77
+    A, B = rng.standard_normal((M, K)), rng.standard_normal((K, N))
+    oa, ob, oc1, oc2 = 0, M * K, M * K + K * N, M * K + K * N + M * N
+    base = dev(np.concatenate([A.ravel(), B.ravel(), np.zeros(2 * M * N + 1)]))
+    L.hsx_bgemm.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_double, C.c_double]
+    dims = np.array([M, N, K, K, N, N], dtype=np.int32)
+    offs = np.array([oa, ob, oc1], dtype=np.int64)
+    assert L.hsx_bgemm(None, 1, hptr(dims), hptr(offs), ptr(base), 0, 0, 1.0, 0.0) == 0
+    dims4, offs4 = [], []
+    for bi in range(2):
+        for bj in range(2):
+            dims4 += [100, 100, K, K, N, N]
+            offs4 += [oa + bi * 100 * K, ob + bj * 100, oc2 + bi * 100 * N + bj * 100]
+    dims4 = np.array(dims4, dtype=np.int32)
+    offs4 = np.array(offs4, dtype=np.int64)
+    assert L.hsx_bgemm(None, 4, hptr(dims4), hptr(offs4), ptr(base), 0, 0, 1.0, 0.0) == 0
+    out = base.cpu().numpy()
+    C1, C2 = out[oc1:oc1 + M * N], out[oc2:oc2 + M * N]
+    assert np.abs(C1.reshape(M, N) - A @ B).max() < 1e-12
+    assert np.array_equal(C1, C2)
 
 
 def test_batched_inverse_with_pivoting(L):
