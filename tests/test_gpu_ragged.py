@@ -255,3 +255,95 @@ def test_ragged_mid_size_like_a_public_data_set():
     assert np.array_equal(perm, cluster_tree(w.F, w.leaf))
     _downstream_parity(ctx, w, perm, oracle_hss_from_export(exp), iters=10, decision=True)
     ctx.close()
+
+
+def _draw_ragged(seed):
+    g = np.random.default_rng(5000 + seed)
+    leaf = int(g.choice([16, 32, 48, 64, 80, 128, 176, 256]))
+    n = int(g.integers(1, 40 * leaf)) if g.random() < 0.8 else int(g.integers(1, 3 * leaf))
+    n = min(n, 5000)
+    r = int(g.choice([1, 2, 3, 5, 8, 13, 28, 29, 57, 84, 96, 97, 112, 113, 123, 200, 300, 384]))
+    s = int(g.choice([32, 100, 128, 256]))
+    F = g.standard_normal((n, r)) * g.uniform(0.3, 2.0, size=r)
+    if g.random() < 0.3:                      # some binary columns: exact ties in the trees
+        k = max(1, r // 3)
+        F[:, :k] = (g.random((n, k)) < 0.3).astype(np.float64)
+    if g.random() < 0.2:                      # a common offset
+        F += g.choice([1e2, -1e4, 1e5])
+    y = np.where(g.random(n) < 0.5, -1.0, 1.0)
+    h = float(np.sqrt(r) * g.choice([0.5, 1.0, 3.0, 10.0]))
+    tol = float(g.choice([1e-2, 1e-3, 1e-4, 3e-5, 1e-5, 1e-6]))
+    opts = {"clustering": int(g.random() < 0.3), "sampling": int(g.random() < 0.3)}
+    if g.random() < 0.4:
+        opts["max_rank"] = int(g.integers(3, max(4, min(s, 2 * leaf))))
+    if g.random() < 0.2:
+        opts["psd_guard"] = 0
+    if opts["sampling"]:
+        opts["ann_neighbours"] = int(g.choice([8, 33, 64]))
+        opts["ann_trees"] = int(g.choice([1, 2, 3]))
+        opts["ann_cell"] = int(g.choice([64, 512]))
+    return dict(n=n, leaf=leaf, r=r, s=s, F=F, y=y, h=h, tol=tol, opts=opts, C=float(g.choice([0.1, 1.0, 10.0])),
+                beta=float(g.choice([0.5, 1.0, 4.0])), Om=g.standard_normal((n, s)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_ragged_problem(seed):
+    """Seeded random problems with any point count (1 .. 5000), 1 .. 384 features, offsets, both trees and both
+    samplings, through the whole path against the oracle."""
+    from gpu_helpers import oracle_hss_from_export
+    p = _draw_ragged(seed)
+    n = p["n"]
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", p["s"])
+    for k, v in p["opts"].items():
+        ctx.hss_set_i64(k, v)
+    F, y = _dev(p["F"]), _dev(p["y"])
+    K = gaussian_kernel(p["F"], p["F"], p["h"])
+    S = ctx.hss_kernel_sample(F, p["h"], _dev(p["Om"])).cpu().numpy()
+    ref = K @ p["Om"]
+    assert np.abs(S - ref).max() <= 1e-12 * max(np.abs(ref).max(), 1e-300), "sample"
+    if p["opts"]["sampling"]:
+        ctx.hss_compress(F, y, p["h"], p["leaf"], p["tol"])
+    else:
+        ctx.hss_compress(F, y, p["h"], p["leaf"], p["tol"], _dev(p["Om"]))
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    tree = cluster_tree_2means(p["F"], p["leaf"], 2) if p["opts"]["clustering"] else cluster_tree(p["F"], p["leaf"])
+    assert np.array_equal(perm, tree), "tree"
+    H = oracle_hss_from_export(exp)
+    st = ctx.hss_stats()
+    g = np.random.default_rng(seed)
+    v = g.standard_normal(n)
+    mv = ctx.hss_matvec(_dev(v)).cpu().numpy()
+    mref = np.empty(n)
+    mref[perm] = ohss.matvec(H, v[perm])
+    assert _rel(mv, mref) <= 1e-12, "matvec"
+    # compression quality: as good as the oracle's on the same sample (or the same neighbour lists)
+    Kp = K[np.ix_(perm, perm)]
+    Kt = ohss.densify(oracle_hss_from_export(exp, with_shift=False))
+    err = np.linalg.norm(Kp - Kt) / np.linalg.norm(Kp)
+    if p["opts"]["sampling"] and tree_depth(n, p["leaf"]) >= 1:
+        idx, dist = ctx.hss_export_neighbours()
+        Ho, _ = oann.compress_ann(p["F"][perm], p["h"], p["leaf"], idx.astype(np.int64), dist, p["s"], p["tol"] / 10,
+                                  1e-8, st["rank_cap"])
+    else:
+        Ho = ohss.compress(p["F"][perm], p["h"], p["leaf"], p["Om"][perm], p["tol"] / 10, 1e-8, st["rank_cap"])
+    err_o = np.linalg.norm(Kp - ohss.densify(Ho)) / np.linalg.norm(Kp)
+    assert err <= max(2.0 * err_o, p["tol"], 1e-12), ("quality", err, err_o)
+    ctx.hss_ulv_factor(p["beta"])
+    x = _dev(v)
+    ctx.hss_ulv_solve(x)
+    Fz = oulv.ulv_factor(H, p["beta"])
+    xref = np.empty(n)
+    xref[perm] = oulv.ulv_solve(Fz, v[perm])
+    cond = np.linalg.cond(ohss.densify(H) + p["beta"] * np.eye(n)) if n <= 1500 else 1.0   # guard off: can be large
+    assert _rel(x.cpu().numpy(), xref) <= 1e-10 * max(1.0, cond / 1e4), ("solve", cond)
+    out = ctx.admm_svm_train(p["C"], p["beta"], 12)
+    oref = oadmm.admm(lambda t: oulv.ulv_solve(Fz, t), p["y"][perm], p["C"], p["beta"], 12)
+    for key in ("x", "z", "mu"):
+        assert _rel(out[key].cpu().numpy()[perm], oref[key]) <= 1e-6 * max(1.0, cond / 1e6), (key, cond)
+    G = p["F"][:min(n, 50)] + 0.1
+    dec = ctx.svm_decision(_dev(G), out["z"], out["bias"]).cpu().numpy()
+    dref = oadmm.decision(p["F"], p["y"], out["z"].cpu().numpy(), out["bias"], G, p["h"])
+    assert np.abs(dec - dref).max() <= 1e-9 * max(1.0, np.abs(dref).max()), "decision"
+    ctx.close()
