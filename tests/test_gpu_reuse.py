@@ -75,3 +75,35 @@ def test_one_context_for_many_problems():
         a, b = got[key], first[key]
         assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, key
     shared.close()
+
+
+def test_out_of_memory_is_an_error_and_the_context_stays_usable():
+    """A compression whose sample buffers cannot be allocated (2^25 points x 2048 columns = 550 GB per buffer) returns
+    HSS_ENOMEM -- no abort, nothing left half-built -- and the same context then compresses a small problem to the
+    bits of a fresh context."""
+    import torch
+    n = 1 << 25
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(1)
+    F = torch.randn((n, 1), dtype=torch.float64, device="cuda:0", generator=g)
+    y = torch.ones(n, dtype=torch.float64, device="cuda:0")
+    ctx = binding.Context()
+    ctx.hss_set_i64("sample_width", 2048)
+    ctx.hss_set_i64("max_rank", 512)
+    with pytest.raises(binding.HssError) as e:
+        ctx.hss_compress(F, y, 1.0, 256, 1e-2)
+    assert e.value.code == binding.HSS_ENOMEM
+    del F, y
+    torch.cuda.empty_cache()
+    with pytest.raises(binding.HssError) as e:                # nothing compressed
+        ctx.hss_ulv_factor(1.0)
+    assert e.value.code == binding.HSS_ESTATE
+    Fs, ys, G = _problem(1000, 8, 5)
+    got = _run(ctx, Fs, ys, G, 1.5, 64, 128, {}, 1.0, 1.0, 8)
+    fresh = binding.Context()
+    ref = _run(fresh, Fs, ys, G, 1.5, 64, 128, {}, 1.0, 1.0, 8)
+    for key in ref:
+        a, b = got[key], ref[key]
+        assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, key
+    fresh.close()
+    ctx.close()
