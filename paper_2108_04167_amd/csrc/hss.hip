@@ -186,12 +186,14 @@ namespace {
 
 // delta = 1.1 * max(0, -lambda_min(K~)) from a Lanczos run on the HSS mat-vec (no re-orthogonalisation:
 // only the extreme Ritz value is used).  The run stops when the smallest Ritz value has moved by less than
-// 1e-3 (relative) over the last four steps, or after 64 steps.
+// 1e-3 (relative) over the last four steps, or after 512 steps.  The number of steps grows with
+// lambda_max / |lambda_min|, i.e. with n: 32-37 steps on the workloads up to n = 262144, 89 at n = 1048576,
+// about 200 at n = 4194304 (where 64 steps still see a positive Ritz value).
 int definiteness_guard(hss_ctx* c) {
     hipStream_t st = c->stream;
     const int64_t n = c->n;
     c->delta = 0.0;
-    const int iters = (int)std::min<int64_t>(n, 64);
+    const int iters = (int)std::min<int64_t>(n, 512);
     DevBuf vprev, vcur;
     HSS_TRY(vprev.reserve(sizeof(double) * n));
     HSS_TRY(vcur.reserve(sizeof(double) * n));

@@ -1,0 +1,64 @@
+"""Four million points (GPU only): workload 4's generator at n = 4 194 304 with neighbour-based sampling through the
+whole path.  No oracle can follow at this size; checked are the properties that hold at any size: the solve's
+residual through the library's mat-vec, the definiteness of the shifted matrix (a long Lanczos run in the test; the
+smallest eigenvalue needs about 200 steps here), ADMM invariants, and a test accuracy near the smaller runs'.
+Skipped when the device does not have the memory free (about 210 GB are used)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2108_04167_amd import binding, synth   # noqa: E402
+
+
+def test_four_million_points():
+    import torch
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 240e9:
+        pytest.skip(f"needs about 210 GB of device memory, {free / 1e9:.0f} GB free")
+    n = 1 << 22
+    w = synth.make_workload(4, n=n)
+    F = torch.tensor(w.F, device="cuda:0")
+    y = torch.tensor(w.y, device="cuda:0")
+    ctx = binding.Context()
+    ctx.hss_set_i64("sampling", 1)
+    ctx.hss_set_i64("sample_width", w.s)
+    rc = ctx.hss_compress(F, y, w.h, w.leaf, w.tol)
+    st = ctx.hss_stats()
+    assert st["levels"] == 14 and st["rank_max"] == 256
+    assert rc & binding.HSS_WSHIFT and st["delta"] > 0.0
+    # lambda_min(K~ + delta I) > 0 and the shift is not far above what is needed: Lanczos on the library's mat-vec
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(0)
+    v = torch.rand(n, dtype=torch.float64, device="cuda:0", generator=g) * 2 - 1
+    v /= v.norm()
+    vp = torch.zeros_like(v)
+    al, be, bprev = [], [], 0.0
+    for j in range(260):
+        wv = ctx.hss_matvec(v)
+        a = float(wv @ v)
+        al.append(a)
+        wv = wv - a * v - bprev * vp
+        bprev = float(wv.norm())
+        be.append(bprev)
+        vp, v = v, wv / bprev
+    T = np.diag(al) + np.diag(be[:-1], 1) + np.diag(be[:-1], -1)
+    lam = float(np.linalg.eigvalsh(T)[0])           # of K~ + delta I
+    assert 0.0 < lam <= 0.12 * st["delta"], (lam, st["delta"])
+    ctx.hss_ulv_factor(w.beta)
+    b = torch.randn(n, dtype=torch.float64, device="cuda:0", generator=g)
+    x = b.clone()
+    ctx.hss_ulv_solve(x)
+    res = float(torch.linalg.norm(ctx.hss_matvec(x) + w.beta * x - b) / torch.linalg.norm(b))
+    assert res <= 1e-10, res
+    out = ctx.admm_svm_train(w.C, w.beta, 60)
+    for key in ("x", "z", "mu"):
+        assert bool(torch.isfinite(out[key]).all()), key
+    assert abs(float((y * out["x"]).sum())) <= 1e-8 * n
+    assert float(out["z"].min()) >= 0.0 and float(out["z"].max()) <= w.C
+    dec = ctx.svm_decision(torch.tensor(w.F_test, device="cuda:0"), out["z"], out["bias"]).cpu().numpy()
+    acc = float(np.mean(np.where(dec >= 0, 1.0, -1.0) == w.y_test)) * 100
+    print(f"[n = {n}] delta {st['delta']:.2f} lambda_min(K~ + delta I) {lam:.3f} solve residual {res:.1e} accuracy {acc:.1f} %")
+    assert acc >= 70.0
+    ctx.close()
