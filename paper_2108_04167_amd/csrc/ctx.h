@@ -48,7 +48,7 @@ struct Level {
     DevBuf BT;                              // B^T (k_b x k_a) per inner node at boff
     bool mv_vec = false;                    // 16-byte loads allowed in this level's mat-vec tables
     DevBuf xt, g;                           // (sum rk) each
-    DevBuf mv_up, mv_dn_u, mv_dn_b, mv_dn_bt, mv_leaf_d;   // GemvItem tables
+    DevBuf mv_up, mv_dn_u, mv_dn_b, mv_leaf_d;   // GemvItem tables (mv_dn_b: B and B^T products of every pair)
     int n_dn_b = 0;
 };
 

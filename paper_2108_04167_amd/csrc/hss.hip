@@ -135,9 +135,9 @@ int build_matvec_tables(hss_ctx* c) {
             b2[i] = GemvItem{BT, lv.xt.as<double>() + lv.koff[a], lv.g.as<double>() + lv.koff[b], nullptr, lv.rk[b], lv.rk[a],
                              lv.rk[a], GEMV_DENSE};
         }
+        b1.insert(b1.end(), b2.begin(), b2.end());      // one table: the two products of a pair write different vectors
         HSS_TRY(upload(c, lv.mv_dn_b, b1));
-        HSS_TRY(upload(c, lv.mv_dn_bt, b2));
-        lv.n_dn_b = pl.N;
+        lv.n_dn_b = 2 * pl.N;
     }
     Level& leafl = c->lev[L];
     std::vector<GemvItem> dd(leafl.N);
@@ -172,7 +172,6 @@ int hss_matvec_perm(hss_ctx* c) {
         // contribution handed down by the parent level (written by the parent's U g), then the coupling
         const double beta = (l == 1) ? 0.0 : 1.0;
         HSS_TRY(bgemv_launch(st, lv.mv_dn_b.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, lv.mv_vec, 1.0, beta));
-        HSS_TRY(bgemv_launch(st, lv.mv_dn_bt.as<GemvItem>(), lv.n_dn_b, lv.maxk, lv.maxk, lv.mv_vec, 1.0, beta));
         if (l < L) HSS_TRY(bgemv_launch(st, lv.mv_dn_u.as<GemvItem>(), lv.N, lv.maxm, lv.maxk, lv.mv_vec, 1.0, 0.0));
     }
     Level& leafl = c->lev[L];
