@@ -132,6 +132,13 @@ def main():
     ap.add_argument("--adaptive-step", type=int, default=128)
     ap.add_argument("--oversample", type=int, default=-1, help="oversampling p (rank cap = width - p; default width/2)")
     ap.add_argument("--max-rank", type=int, default=0)
+    ap.add_argument("--tol", type=float, default=0.0, help="override the workload's tolerance (relative truncation "
+                    "threshold = tol / 10)")
+    ap.add_argument("--abs-tol", type=float, default=-1.0, help="absolute truncation threshold (default 1e-8)")
+    ap.add_argument("--leaf", type=int, default=0, help="override the workload's largest leaf size")
+    ap.add_argument("--paper-table1", action="store_true",
+                    help="the parameter set under the paper's first results table: relative threshold 1, absolute 0.1, "
+                         "rank cap 200, 64 approximate neighbours (neighbour-based sampling), leaf 128")
     ap.add_argument("--neighbours", action="store_true",
                     help="neighbour-based sampling (the paper's own compressor) instead of the random sample K*Omega")
     ap.add_argument("--ann-trees", type=int, default=3)
@@ -163,6 +170,15 @@ def main():
     F = torch.tensor(w.F, device=dev)
     y = torch.tensor(w.y, device=dev)
     ctx = binding.Context()
+    if args.paper_table1:
+        args.neighbours, args.tol, args.abs_tol, args.max_rank, args.leaf = True, 10.0, 0.1, 200, 128
+        args.sample_width = args.sample_width or 256
+    if args.tol > 0.0:
+        w.tol = args.tol
+    if args.leaf:
+        w.leaf = args.leaf
+    if args.abs_tol >= 0.0:
+        ctx.hss_set_f64("abs_tol", args.abs_tol)
     if args.sample_width:
         w.s = args.sample_width
     ctx.hss_set_i64("sample_width", w.s)
@@ -237,7 +253,8 @@ def main():
 
     # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised under profiles/ (scaled by
     # a plain copy of known size); they hold for the default workload and the kernels they were taken on only.
-    default_path = not (args.neighbours or args.sample_width or args.adaptive_start or args.no_merge_top)
+    default_path = not (args.neighbours or args.sample_width or args.adaptive_start or args.no_merge_top or args.tol > 0.0
+                        or args.leaf or args.abs_tol >= 0.0)
     tr_sample, note_sample = measured_traffic(args.cfg, n, "sample_kernel") if default_path else (None, "non-default options")
     tr_solve, note_solve = measured_traffic(args.cfg, n, "solve") if default_path else (None, "non-default options")
 

@@ -254,7 +254,7 @@ int definiteness_guard(hss_ctx* c) {
 int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int r, double h, int leaf, double tol,
                       const double* Omega, int s_in) {
     if (!c || !F || !y) return HSS_EINVAL;
-    if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol < 1.0)) return HSS_EINVAL;
+    if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol <= 10.0)) return HSS_EINVAL;
     if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
     if (r > MAX_FEATURES || leaf > 1024) return HSS_EUNSUPPORTED;
     const int L = tree_depth(n, leaf);                       // any n: leaves of ceil or floor of n / 2^L points

@@ -242,3 +242,45 @@ def test_features_with_a_large_common_offset(offset):
     assert np.array_equal(idx, ri) and np.array_equal(dist, rd)
     ctx2.close()
     ctx.close()
+
+
+@pytest.mark.parametrize("cfg,n", [(2, 8192), (4, 5000)])
+def test_loosest_truncation_of_the_papers_first_table(cfg, n):
+    """The parameter set under the paper's first results table: relative truncation threshold 1, absolute 0.1, rank cap
+    200, 64 approximate neighbours per point.  A relative threshold of 1 keeps one pivot per block (the first pivot is
+    always kept), so every rank is 1 and the compressed matrix is the leaf diagonal blocks plus rank-one couplings;
+    the path on that matrix against the oracle as usual."""
+    from gpu_helpers import oracle_hss_from_export
+    w = synth.make_workload(cfg, n=n)
+    ctx = binding.Context()
+    ctx.hss_set_i64("sampling", 1)
+    ctx.hss_set_i64("ann_neighbours", 64)
+    ctx.hss_set_i64("sample_width", 256)
+    ctx.hss_set_i64("max_rank", 200)
+    ctx.hss_set_f64("abs_tol", 0.1)
+    ctx.hss_compress(_dev(w.F), _dev(w.y), w.h, 128, 10.0)
+    exp = ctx.hss_export()
+    assert (exp["ranks"][1:] == 1).all()
+    perm = exp["perm"]
+    H = oracle_hss_from_export(exp)
+    rng = np.random.default_rng(0)
+    v = rng.standard_normal(n)
+    mv = ctx.hss_matvec(_dev(v)).cpu().numpy()
+    mref = np.empty(n)
+    mref[perm] = ohss.matvec(H, v[perm])
+    assert _rel(mv, mref) <= 1e-12
+    ctx.hss_ulv_factor(w.beta)
+    x = _dev(v)
+    ctx.hss_ulv_solve(x)
+    Fz = oulv.ulv_factor(H, w.beta)
+    xref = np.empty(n)
+    xref[perm] = oulv.ulv_solve(Fz, v[perm])
+    assert _rel(x.cpu().numpy(), xref) <= 1e-10
+    out = ctx.admm_svm_train(w.C, w.beta, 30)
+    oref = oadmm.admm(lambda t: oulv.ulv_solve(Fz, t), w.y[perm], w.C, w.beta, 30)
+    for key in ("x", "z", "mu"):
+        assert _rel(out[key].cpu().numpy()[perm], oref[key]) <= 1e-6, key
+    dec = ctx.svm_decision(_dev(w.F_test[:500]), out["z"], out["bias"]).cpu().numpy()
+    acc = float(np.mean(np.where(dec >= 0, 1.0, -1.0) == w.y_test[:500])) * 100
+    print(f"[table-1 parameters, cfg{cfg} n={n}] all ranks 1, delta {exp['delta']:.3f}, accuracy after 30 iterations {acc:.1f} %")
+    ctx.close()
