@@ -107,7 +107,8 @@ int build_solve_tables(hss_ctx* c) {
         }
         // measured on the widest level of the n = 262144 workload (1.07 GB per sweep): 2 rows per wavefront
         // 157 us, 4 rows 163 us, 8 rows 177 us -- many short-lived workgroups beat few long ones here
-        int rpw = 2;
+        // rows of at most 128 columns are one 16-byte load per lane: 4 of them per wavefront keep more bytes in flight
+        int rpw = lv.maxm <= 128 ? 4 : 2;
         while (rpw > 1 && rows_total / (4 * rpw) < 4096) rpw >>= 1;
         lv.rows_per_wave = rpw;
         lv.vec = even;
