@@ -100,7 +100,8 @@ void hss_destroy(hss_ctx* ctx);
  *   "clustering_iterations"  Lloyd steps of that pass, 0 .. 64 (default 2)
  *
  * Definiteness
- *   "psd_guard"          1 (default): after compression estimate lambda_min(K~) and, if negative, add
+ *   "psd_guard"          1 (default): after compression estimate lambda_min(K~) (Lanczos on the HSS mat-vec until the
+ *                        smallest Ritz value settles, at most 512 steps) and, if negative, add
  *                        delta = 1.1*|lambda_min| to the diagonal so that the approximate problem (eq. 8) stays
  *                        convex, as Algorithm 3 presupposes; 0: off
  *
