@@ -147,7 +147,7 @@ int hss_kernel_sample_noalloc(hss_ctx* ctx, const double* F_dev, int64_t n, int3
 /* HSS compression of K(F,F) (Algorithm 3, first line): cluster tree (balanced bisection; option "clustering"),
  * sampling of the off-diagonal block rows (S = K Omega, or the neighbour-based sample; option "sampling"),
  * interpolative decompositions level by level.  F (dev, n x r), y (dev, n).  Any n >= 1; `leaf` = the largest leaf
- * size, a multiple of 16 with 16 <= leaf <= 1024; 1 <= r <= 384, h > 0, 0 < tol <= 10
+ * size, 2 <= leaf <= 1024; 1 <= r <= 384, h > 0, 0 < tol <= 10
  * (tol/10 is the relative truncation threshold below; tol = 10 keeps one pivot per block, the loosest setting of the
  * paper's Table 1: relative 1, absolute 0.1 through "abs_tol").
  * Shape of the tree: depth L = the smallest one with ceil(n / 2^L) <= leaf; a node of p points gives the lower

@@ -255,7 +255,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
                       const double* Omega, int s_in) {
     if (!c || !F || !y) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(tol > 0.0) || !(tol <= 10.0)) return HSS_EINVAL;
-    if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
+    if (leaf < 2) return HSS_EINVAL;
     if (r > MAX_FEATURES || leaf > 1024) return HSS_EUNSUPPORTED;
     const int L = tree_depth(n, leaf);                       // any n: leaves of ceil or floor of n / 2^L points
     if (L > 24) return HSS_EUNSUPPORTED;
@@ -648,7 +648,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
                     const int32_t* J, const double* B, double delta) {
     if (!c || !F || !y || !perm_h || !sizes || !ranks || !D || !U || !J || !B) return HSS_EINVAL;
     if (n < 1 || r < 1 || !(h > 0.0) || !(delta >= 0.0) || !(delta <= 1.7976931348623157e308)) return HSS_EINVAL;
-    if (leaf < 16 || leaf % 16 != 0) return HSS_EINVAL;
+    if (leaf < 2) return HSS_EINVAL;
     if (r > MAX_FEATURES || leaf > 1024) return HSS_EUNSUPPORTED;
     const int L = tree_depth(n, leaf);
     if (L > 24) return HSS_EUNSUPPORTED;

@@ -275,7 +275,7 @@ def test_error_paths():
     with pytest.raises(binding.HssError) as e:
         ctx.hss_ulv_factor(1.0)
     assert e.value.code == binding.HSS_ESTATE
-    for bad in (dict(h=-1.0), dict(leaf=8), dict(tol=0.0), dict(tol=10.5), dict(leaf=40)):
+    for bad in (dict(h=-1.0), dict(leaf=1), dict(tol=0.0), dict(tol=10.5), dict(leaf=0)):
         kw = dict(h=w.h, leaf=w.leaf, tol=w.tol)
         kw.update(bad)
         with pytest.raises(binding.HssError) as e:

@@ -70,6 +70,9 @@ SHAPES = {
     "n15_one_leaf": (1, 15, 16, 128, {}),                # a single leaf below the leaf size
     "n17_two_leaves": (1, 17, 16, 128, {}),
     "n3001_r54": (3, 3001, 256, 512, {}),
+    "n1000_leaf10": (1, 1000, 10, 128, {}),              # leaf sizes that are no multiple of anything: 7 and 8
+    "n1234_leaf100": (2, 1234, 100, 128, {}),
+    "n500_leaf3": (1, 500, 3, 128, {"max_rank": 2}),     # leaves of 1 and 2 points
     "n5000_r90": (5, 5000, 256, 512, {}),
     "n4099_leaf1024": (4, 4099, 1024, 512, {}),
     "n1500_odd_ranks": (1, 1500, 64, 128, {"max_rank": 37}),
