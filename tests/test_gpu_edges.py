@@ -1,6 +1,7 @@
-"""The limits of the library's shapes (GPU only): feature counts 1, 28/29 (a padding boundary) and 96 (the
-maximum), leaf sizes 16 and 1024 (the maximum; smaller leaves in test_gpu_ragged.py), sample width 512 with the rank cap at its maximum 512
-(node sizes up to 1024, the solve kernel's widest block), and odd ranks (scalar-load kernels).  Each case checks
+"""The limits of the library's shapes (GPU only): feature counts 1, 28/29 (a padding boundary) and 96 (more features
+in test_gpu_wide_features.py), leaf sizes 16 and 1024 (the maximum; smaller leaves in test_gpu_ragged.py), sample width 512
+with the rank cap at its maximum 512 (node sizes up to 1024, the solve kernel's widest block), and odd ranks
+(scalar-load kernels).  Each case checks
 S = K Omega, the mat-vec, the ULV solve and a short ADMM run against the oracle on the exported matrix."""
 import copy
 
