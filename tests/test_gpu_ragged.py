@@ -69,6 +69,9 @@ SHAPES = {
     "n37_leaf16": (1, 37, 16, 128, {}),                  # leaves of 10, 9, 9, 9
     "n15_one_leaf": (1, 15, 16, 128, {}),                # a single leaf below the leaf size
     "n17_two_leaves": (1, 17, 16, 128, {}),
+    "n1_single_point": (1, 1, 16, 128, {}),
+    "n2_two_points": (1, 2, 16, 128, {}),
+    "n3_leaf2": (1, 3, 2, 128, {}),                      # leaves of 2 and 1 points
     "n3001_r54": (3, 3001, 256, 512, {}),
     "n1000_leaf10": (1, 1000, 10, 128, {}),              # leaf sizes that are no multiple of anything: 7 and 8
     "n1234_leaf100": (2, 1234, 100, 128, {}),
