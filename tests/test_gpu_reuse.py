@@ -107,3 +107,24 @@ def test_out_of_memory_is_an_error_and_the_context_stays_usable():
         assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, key
     fresh.close()
     ctx.close()
+
+
+def test_destroy_returns_the_device_memory():
+    """Create, use and destroy 40 contexts: the free device memory afterwards is what it was before (within the
+    allocator's granularity), so nothing the library allocates outlives hss_destroy."""
+    import torch
+    Fs, ys, G = _problem(3001, 20, 3)
+    warm = binding.Context()
+    _run(warm, Fs, ys, G, 2.0, 128, 256, {"sampling": 1}, 1.0, 1.0, 3)      # first use: code objects, arena, streams
+    warm.close()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    before, _ = torch.cuda.mem_get_info()
+    for i in range(40):
+        ctx = binding.Context()
+        _run(ctx, Fs, ys, G, 2.0, 128, 256, {"sampling": i % 2, "clustering": (i // 2) % 2}, 1.0, 1.0, 3)
+        ctx.close()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    after, _ = torch.cuda.mem_get_info()
+    assert before - after < 64 << 20, (before, after)
