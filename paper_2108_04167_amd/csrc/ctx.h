@@ -52,6 +52,23 @@ struct Level {
     int n_dn_b = 0;
 };
 
+// FP32 copies of the generators and the item tables of the mat-vec on them (matvec32.hip): alive during the
+// definiteness guard only.
+struct Matvec32 {
+    struct Lev {
+        float *U = nullptr, *UT = nullptr, *B = nullptr, *BT = nullptr;   // copies of the level's U, U^T and of the
+                                            // parent level's B, B^T, inside `pool`
+        const GemvItem32 *up = nullptr, *dn_u = nullptr, *dn_b = nullptr;   // item tables, in the context's upload arena
+        int n_dn_b = 0;
+        bool vec4 = false;                  // 16-byte loads allowed (sizes and ranks multiples of 4)
+    };
+    std::vector<Lev> lev;
+    DevBuf pool;                            // all FP32 copies in one allocation
+    float* D = nullptr;
+    const GemvItem32* leaf_d = nullptr;
+    bool leaves4 = false, ready = false;
+};
+
 struct hss_ctx {
     hipStream_t stream = nullptr;
     hipStream_t gstream = nullptr;          // the library's own stream for graph capture and replay (default priority)
@@ -99,6 +116,7 @@ struct hss_ctx {
     DescArena arena;
     // fixed vectors (cluster-tree order)
     DevBuf mv_x, mv_y;                      // mat-vec in / out
+    Matvec32 mv32;
     DevBuf v_x, v_z, v_mu, v_t, v_w, v_e, v_u;   // ADMM
     DevBuf partial, scal;                   // reduction partials (4*VEC_BLOCKS), device scalars (16)
     // stats
@@ -128,6 +146,10 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
                     const int64_t* perm_h, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
                     const int32_t* J, const double* B, double delta);
 int hss_matvec_perm(hss_ctx* c);           // mv_y = K~' mv_x  (cluster-tree order, shift included)
+// matvec32.hip
+int build_matvec32(hss_ctx* c);
+void release_matvec32(hss_ctx* c);
+int hss_matvec_perm32(hss_ctx* c);
 // ulv.hip
 int ulv_factor_impl(hss_ctx* c, double beta);
 int ulv_solve_perm(hss_ctx* c, const double* b_perm, double* x_perm);   // cluster-tree order; may alias

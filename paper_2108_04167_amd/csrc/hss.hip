@@ -193,6 +193,18 @@ int definiteness_guard(hss_ctx* c) {
     const int64_t n = c->n;
     c->delta = 0.0;
     const int iters = (int)std::min<int64_t>(n, 512);
+    // the mat-vec of the run reads FP32 copies of the generators (half the traffic; matvec32.hip); if they do not fit
+    // into memory, the FP64 mat-vec
+    const bool use32 = build_matvec32(c) == HSS_OK;
+    if (!use32) release_matvec32(c);
+    struct Release32 {      // the item tables live in the upload arena: drained and reset on every way out
+        hss_ctx* c;
+        ~Release32() {
+            (void)hipStreamSynchronize(c->stream);
+            c->arena.reset();
+            release_matvec32(c);
+        }
+    } release32{c};
     DevBuf vprev, vcur;
     HSS_TRY(vprev.reserve(sizeof(double) * n));
     HSS_TRY(vcur.reserve(sizeof(double) * n));
@@ -219,7 +231,7 @@ int definiteness_guard(hss_ctx* c) {
     double bprev = 0.0;
     for (int j = 0; j < iters; ++j) {
         HIP_TRY(hipMemcpyAsync(c->mv_x.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
-        HSS_TRY(hss_matvec_perm(c));
+        HSS_TRY(use32 ? hss_matvec_perm32(c) : hss_matvec_perm(c));
         HSS_TRY(vec_dot(st, w, vcur.as<double>(), n, part, scal));
         double a;
         HIP_TRY(hipMemcpyAsync(&a, scal, sizeof(double), hipMemcpyDeviceToHost, st));

@@ -21,6 +21,14 @@ struct GemvItem {            // y = alpha * op x + beta * y
     int32_t M, N, lda, mode;
 };
 
+struct GemvItem32 {          // the same with the matrix in FP32 (vectors and sums FP64)
+    const float*  A;
+    const double* x;
+    double*       y;
+    const int32_t* perm;
+    int32_t M, N, lda, mode;
+};
+
 // rows_per_wave in {1, 2, 4}: a workgroup (4 wavefronts) takes 4 * rows_per_wave rows of one node.
 // nrhs in {1, 2, 4} interleaved right-hand sides; `pool` is the allocation all vector pointers of the item
 // tables point into (a pointer p of the tables stands for pool + (p - pool) * nrhs).
