@@ -52,8 +52,9 @@ struct Level {
     int n_dn_b = 0;
 };
 
-// FP32 copies of the generators and the item tables of the mat-vec on them (matvec32.hip): alive during the
-// definiteness guard only.
+// FP32 copies of the generators and the item tables of the mat-vec on them (matvec32.hip): filled for the
+// definiteness guard's run.  The pool stays allocated between compressions and only grows (freeing tens of
+// gigabytes right before the factorization allocates its own made those allocations take seconds).
 struct Matvec32 {
     struct Lev {
         float *U = nullptr, *UT = nullptr, *B = nullptr, *BT = nullptr;   // copies of the level's U, U^T and of the
@@ -63,7 +64,7 @@ struct Matvec32 {
         bool vec4 = false;                  // 16-byte loads allowed (sizes and ranks multiples of 4)
     };
     std::vector<Lev> lev;
-    DevBuf pool;                            // all FP32 copies in one allocation
+    DevBuf pool;                            // all FP32 copies in one allocation, kept until the context is destroyed
     float* D = nullptr;
     const GemvItem32* leaf_d = nullptr;
     bool leaves4 = false, ready = false;

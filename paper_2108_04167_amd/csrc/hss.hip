@@ -194,7 +194,7 @@ int definiteness_guard(hss_ctx* c) {
     c->delta = 0.0;
     const int iters = (int)std::min<int64_t>(n, 512);
     // the mat-vec of the run reads FP32 copies of the generators (half the traffic; matvec32.hip); if they do not fit
-    // into memory, the FP64 mat-vec
+    // into memory, the FP64 mat-vec.  The copies' pool stays with the context.
     const bool use32 = build_matvec32(c) == HSS_OK;
     if (!use32) release_matvec32(c);
     struct Release32 {      // the item tables live in the upload arena: drained and reset on every way out

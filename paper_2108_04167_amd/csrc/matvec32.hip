@@ -206,8 +206,11 @@ int build_matvec32(hss_ctx* c) {
     return HSS_OK;
 }
 
+// Drops the tables; the pool of copies stays allocated for the next compression of the context (it only grows).
 void release_matvec32(hss_ctx* c) {
+    DevBuf keep = std::move(c->mv32.pool);
     c->mv32 = Matvec32();
+    c->mv32.pool = std::move(keep);
 }
 
 // mv_y = (K~ + delta I) mv_x with the FP32 generator copies (cluster-tree order)
