@@ -134,6 +134,30 @@ def test_wide_features_neighbour_based(n, r, leaf, k, trees):
     ctx.close()
 
 
+def test_wide_features_adaptive_width():
+    """Adaptive sample width over the stripe path: the column windows of Omega (offset, leading dimension of the
+    whole matrix) give the same widths, redone nodes, ranks and error as the oracle's adaptive compression."""
+    from gpu_helpers import oracle_hss_from_export
+    n, r, leaf, s, h, tol = 1500, 200, 64, 384, 2.0, 1e-3
+    F, y, g = _data(n, r, 11)
+    Om = g.standard_normal((n, s))
+    ctx = binding.Context()
+    ctx.hss_set_i64("adaptive_start", 128)
+    ctx.hss_compress(_dev(F), _dev(y), h, leaf, tol, _dev(Om))
+    st = ctx.hss_stats()
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    assert np.array_equal(perm, cluster_tree(F, leaf))
+    K = gaussian_kernel(F[perm], F[perm], h)
+    err = np.linalg.norm(K - ohss.densify(oracle_hss_from_export(exp, with_shift=False))) / np.linalg.norm(K)
+    Ho, info = ohss.compress_adaptive(F[perm], h, leaf, Om[perm], tol / 10.0, 1e-8, s0=128, step=128)
+    err_o = np.linalg.norm(K - ohss.densify(Ho)) / np.linalg.norm(K)
+    assert st["sample_width_used"] == info["width"] and st["nodes_redone"] == info["redone"]
+    assert np.array_equal(exp["ranks"], Ho.ranks())
+    assert abs(err - err_o) <= 1e-9 * err_o
+    ctx.close()
+
+
 def test_feature_limit():
     ctx = binding.Context()
     F = np.zeros((256, 385))
