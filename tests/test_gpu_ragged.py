@@ -353,3 +353,69 @@ def test_random_ragged_problem(seed):
     dref = oadmm.decision(p["F"], p["y"], out["z"].cpu().numpy(), out["bias"], G, p["h"])
     assert np.abs(dec - dref).max() <= 1e-9 * max(1.0, np.abs(dref).max()), "decision"
     ctx.close()
+
+
+def _draw_solve_options(seed):
+    g = np.random.default_rng(9000 + seed)
+    leaf = int(g.choice([8, 16, 32, 48, 64, 100, 128, 256]))
+    n = int(g.integers(1, 30 * leaf)) if g.random() < 0.85 else int(g.integers(1, 3 * leaf))
+    n = min(n, 4000)
+    r = int(g.choice([1, 2, 5, 8, 18, 54, 90, 123]))
+    s = int(g.choice([32, 100, 128, 256]))
+    F = g.standard_normal((n, r)) * g.uniform(0.3, 2.0, size=r)
+    y = np.where(g.random(n) < 0.5, -1.0, 1.0)
+    h = float(np.sqrt(r) * g.choice([1.0, 3.0, 10.0]))
+    tol = float(g.choice([1e-2, 1e-3, 1e-4, 1e-6]))
+    opts = {"merge_top": int(g.random() < 0.5), "graph": int(g.random() < 0.5), "cache_basis": int(g.random() < 0.5)}
+    if g.random() < 0.4:
+        opts["max_rank"] = int(g.integers(3, max(4, min(s, 2 * leaf))))
+    if g.random() < 0.3:
+        opts["adaptive_start"] = 128
+        opts["adaptive_step"] = int(g.choice([128, 256]))
+        s = int(g.choice([256, 384, 512]))
+    if g.random() < 0.3:
+        opts["clustering"] = 1
+    betas = [float(b) for b in g.choice([0.25, 0.5, 1.0, 2.0, 8.0], size=3)]
+    return dict(n=n, leaf=leaf, r=r, s=s, F=F, y=y, h=h, tol=tol, opts=opts, betas=betas,
+                Cs=[0.1, 1.0, 10.0][:int(g.integers(1, 4))], nrhs=int(g.integers(1, 6)), Om=g.standard_normal((n, s)))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_ragged_solve_options(seed):
+    """Seeded random problems on uneven trees with the options of the solve drawn at random (merged top, graph replay,
+    cached bases across beta, adaptive width, either tree): three factorizations in a row on one compression, several
+    right-hand sides solved twice each (the second call replays), several box bounds in lockstep and one alone, all
+    against the oracle's ULV and ADMM on the exported matrix."""
+    from gpu_helpers import oracle_hss_from_export
+    p = _draw_solve_options(seed)
+    n = p["n"]
+    ctx = binding.Context()
+    for k, v in p["opts"].items():
+        ctx.hss_set_i64(k, v)
+    ctx.hss_compress(_dev(p["F"]), _dev(p["y"]), p["h"], p["leaf"], p["tol"], _dev(p["Om"]))
+    exp = ctx.hss_export()
+    perm = exp["perm"]
+    H = oracle_hss_from_export(exp)
+    g = np.random.default_rng(seed)
+    cond = np.linalg.cond(ohss.densify(H) + min(p["betas"]) * np.eye(n)) if n <= 1500 else 1.0
+    for beta in p["betas"]:
+        ctx.hss_ulv_factor(beta)
+        Fz = oulv.ulv_factor(H, beta)
+        V = g.standard_normal((p["nrhs"], n))
+        for rep in range(2):
+            X = _dev(V if p["nrhs"] > 1 else V[0])
+            ctx.hss_ulv_solve(X)
+            X = X.cpu().numpy().reshape(p["nrhs"], n)
+            for j in range(p["nrhs"]):
+                xref = np.empty(n)
+                xref[perm] = oulv.ulv_solve(Fz, V[j][perm])
+                assert _rel(X[j], xref) <= 1e-10 * max(1.0, cond / 1e4), ("solve", beta, rep, j, cond)
+        out = ctx.admm_svm_train_multi(p["Cs"], beta, 10)
+        for ci, Cb in enumerate(p["Cs"]):
+            oref = oadmm.admm(lambda t: oulv.ulv_solve(Fz, t), p["y"][perm], Cb, beta, 10)
+            for key in ("x", "z", "mu"):
+                assert _rel(out[key].cpu().numpy()[ci][perm], oref[key]) <= 1e-6 * max(1.0, cond / 1e6), (key, beta, Cb)
+        one = ctx.admm_svm_train(p["Cs"][-1], beta, 10)
+        for key in ("x", "z", "mu"):
+            assert _rel(one[key].cpu().numpy()[perm], oref[key]) <= 1e-6 * max(1.0, cond / 1e6), (key, beta)
+    ctx.close()
