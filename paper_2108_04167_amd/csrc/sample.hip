@@ -11,7 +11,9 @@
 //      accumulator block (128 VGPRs at CT = 4) and streams its own columns of Omega straight from
 //      HBM/L2 into registers one j-block ahead of use (each Omega element is used by exactly
 //      WR wavefronts of the workgroup, so LDS staging would not add reuse).
-// The K tile and the F_j tile are double buffered in LDS: one barrier per j-block.
+// The K tile and the F_j tile are double buffered in LDS: one barrier per j-block, placed before the last
+// contraction k-step of the block (whose operands are in registers by then), so that no wavefront leaves the
+// barrier with nothing but LDS reads to wait for.
 #include "common.h"
 
 namespace {
@@ -174,36 +176,56 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
     __syncthreads();
 
     double fj[MAXF];
-    double nuj_next = 0.0;
+    double nuj_raw = 0.0;
+    // K-tile operands of the next contraction k-step, fetched from LDS one step ahead and carried over the
+    // barrier: the barrier sits between k-steps 6 and 7, so every wavefront leaves it with sixteen MFMAs whose
+    // operands are already in registers, and fetches the first operands of the next tile behind them
+    double an[4];
+    {
+        const double* Kt0 = K_s + wr * 64 + lr + lk * LDK;
+        an[0] = Kt0[0]; an[1] = Kt0[16]; an[2] = Kt0[32]; an[3] = Kt0[48];
+    }
     for (int jb = 0; jb < NJ; ++jb) {
         const int cur = jb & 1, nxt = cur ^ 1;
-        // stage F_j tile jb+2 in registers (stored to LDS at the end of this iteration)
+        // stage F_j tile jb+2 in registers (stored to LDS before this iteration's barrier)
         const int jb2 = jb + 2 < NJ ? jb + 2 : NJ - 1;
         const double* fsrc = Fp + (size_t)jb2 * TILE + tid;
 #pragma unroll
         for (int u = 0; u < MAXF; ++u)
             if ((u + 1) * 512 <= TILE || tid + u * 512 < TILE) fj[u] = fsrc[u * 512];
-        if (tid < BN) nuj_next = -nu[jb2 * BN + tid] * inv2h2;
+        nuj_raw = nu[jb2 * BN + (tid & (BN - 1))];
 
-        // Contraction with K tile jb, software pipelined: the K-tile operands of k-step ks+1 are fetched from
-        // LDS before the MFMAs of step ks are issued.  The Gram tile of K tile jb+1 is spread over k-steps
-        // 0-3 and its exponentials over steps 4-7 (one accumulator register each), so vector-ALU work and
-        // Gram MFMAs sit between the contraction MFMAs instead of forming a workgroup-wide phase after the
-        // barrier.  (After the last column block the extra tile is computed from the clamped F_j tile and
-        // never used.)
+        // Contraction with K tile jb.  The Gram tile of K tile jb+1 is spread over k-steps 0-2 and its
+        // exponentials over steps 3-6 (one accumulator register each), so vector-ALU work and Gram MFMAs sit
+        // between the contraction MFMAs.  (After the last column block the extra tile is computed from the
+        // clamped F_j tile and never used.)
         const double* Kt = K_s + cur * BN * LDK + wr * 64 + lr + lk * LDK;
+        const double* Ktn = K_s + nxt * BN * LDK + wr * 64 + lr + lk * LDK;
         const double* Fjn = Fj_s + nxt * BN * LDF;
         // Omega: block jb+1 is clamped to the last block (loads past it are never consumed)
         const size_t wrap = (jb + 1 < NJ) ? 0 : (size_t)BN * s_pad;
         v4d g[WR];
 #pragma unroll
         for (int u = 0; u < WR; ++u) g[u] = (v4d){0.0, 0.0, 0.0, 0.0};
-        double an[4] = {Kt[0], Kt[16], Kt[32], Kt[48]};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
+            if (ks == 7) {
+                // publish F_j tile jb+2 into the buffer tile jb used; every read of K tile jb has been issued
+                // (the operands of k-step 7 are in registers) and K tile jb+1 is complete
+#pragma unroll
+                for (int u = 0; u < MAXF; ++u) {
+                    const int idx = tid + u * 512;
+                    if ((u + 1) * 512 <= TILE || idx < TILE) {
+                        const int rr = idx / RP, cc = idx - rr * RP;
+                        Fj_s[(cur * BN + rr) * LDF + cc] = fj[u];
+                    }
+                }
+                if (tid < BN) nuj_s[cur * BN + tid] = -nuj_raw * inv2h2;
+                __syncthreads();
+            }
             const double a0 = an[0], a1 = an[1], a2 = an[2], a3 = an[3];
-            if (ks < 7) {
-                const double* kp = Kt + (ks + 1) * 4 * LDK;
+            {
+                const double* kp = ks < 7 ? Kt + (ks + 1) * 4 * LDK : Ktn;
                 an[0] = kp[0]; an[1] = kp[16]; an[2] = kp[32]; an[3] = kp[48];
             }
 #pragma unroll
@@ -216,22 +238,10 @@ __global__ __launch_bounds__(512) void sample_kernel(const double* __restrict__ 
             }
             if (ks + RING < 8) load_omega(op + (ks + RING) * step_elems, ks % RING);
             else load_omega(op + (ks + RING) * step_elems - wrap, ks % RING);
-            if (ks < 4) gram_steps(g, Fjn, (NK4 * ks) / 4, (NK4 * (ks + 1)) / 4);
-            else exp_store(g, nxt, ks - 4);
+            if (ks < 3) gram_steps(g, Fjn, (NK4 * ks) / 3, (NK4 * (ks + 1)) / 3);
+            else if (ks < 7) exp_store(g, nxt, ks - 3);
         }
         op += (size_t)BN * s_pad;
-
-        // publish F_j tile jb+2 into the buffer tile jb used
-#pragma unroll
-        for (int u = 0; u < MAXF; ++u) {
-            const int idx = tid + u * 512;
-            if ((u + 1) * 512 <= TILE || idx < TILE) {
-                const int rr = idx / RP, cc = idx - rr * RP;
-                Fj_s[(cur * BN + rr) * LDF + cc] = fj[u];
-            }
-        }
-        if (tid < BN) nuj_s[cur * BN + tid] = nuj_next;
-        __syncthreads();
     }
 
     // acc[rt][ct][v]  ->  S[row0 + wr*64 + rt*16 + 4*v + lk][col0 + CT*lr + ct]
