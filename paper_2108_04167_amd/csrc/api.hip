@@ -77,6 +77,7 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
                       int32_t s, double* S_out_dev) {
     if (!ctx || !F_dev || !Omega_dev || !S_out_dev || n < 1 || r < 1 || s < 1 || !(h > 0.0)) return HSS_EINVAL;
     if (r > MAX_FEATURES) return HSS_EUNSUPPORTED;
+    CacheScope cache_scope(&ctx->cache);
     hipStream_t st = ctx->stream;
     const int64_t n_pad = round_up(n, 256);
     const int r_pad = feature_pad(r), s_pad = (int)round_up(s, 128);
@@ -102,24 +103,30 @@ int hss_kernel_sample(hss_ctx* ctx, const double* F_dev, int64_t n, int32_t r, d
 
 int hss_compress(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,
                  double tol) {
+    if (!ctx) return HSS_EINVAL;
+    CacheScope cache_scope(&ctx->cache);
     return hss_compress_impl(ctx, F_dev, y_dev, n, r, h, leaf, tol, nullptr, 0);
 }
 
 int hss_compress_with_samples(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h,
                               int32_t leaf, double tol, const double* Omega_dev, int32_t s) {
-    if (!Omega_dev) return HSS_EINVAL;
+    if (!Omega_dev || !ctx) return HSS_EINVAL;
+    CacheScope cache_scope(&ctx->cache);
     return hss_compress_impl(ctx, F_dev, y_dev, n, r, h, leaf, tol, Omega_dev, s);
 }
 
 int hss_import(hss_ctx* ctx, const double* F_dev, const double* y_dev, int64_t n, int32_t r, double h, int32_t leaf,
                const int64_t* perm, const int32_t* sizes, const int32_t* ranks, const double* D, const double* U,
                const int32_t* J, const double* B, double delta) {
+    if (!ctx) return HSS_EINVAL;
+    CacheScope cache_scope(&ctx->cache);
     return hss_import_impl(ctx, F_dev, y_dev, n, r, h, leaf, perm, sizes, ranks, D, U, J, B, delta);
 }
 
 int hss_error_estimate(hss_ctx* c, int32_t nprobe, uint64_t seed, double* rel_err_out) {
     if (!c || !rel_err_out || nprobe < 1 || nprobe > 128) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
+    CacheScope cache_scope(&c->cache);
     hipStream_t st = c->stream;
     const int64_t n = c->n, n_pad = c->n_pad;
     // K Z through the 16-column product when the probes fit, else through a 128-column block of the sampling kernel
@@ -158,11 +165,16 @@ int hss_error_estimate(hss_ctx* c, int32_t nprobe, uint64_t seed, double* rel_er
     return HSS_OK;
 }
 
-int hss_ulv_factor(hss_ctx* ctx, double beta) { return ulv_factor_impl(ctx, beta); }
+int hss_ulv_factor(hss_ctx* ctx, double beta) {
+    if (!ctx) return HSS_EINVAL;
+    CacheScope cache_scope(&ctx->cache);
+    return ulv_factor_impl(ctx, beta);
+}
 
 int hss_ulv_solve(hss_ctx* c, double* rhs, int32_t nrhs) {
     if (!c || !rhs || nrhs < 1) return HSS_EINVAL;
     if (!c->compressed || !c->factored) return HSS_ESTATE;
+    CacheScope cache_scope(&c->cache);
     hipStream_t st = c->stream;
     const int64_t* perm = c->perm.as<int64_t>();
     // groups of up to MAX_NRHS columns share one pass over the factors
@@ -181,6 +193,7 @@ int hss_ulv_solve(hss_ctx* c, double* rhs, int32_t nrhs) {
 int hss_matvec(hss_ctx* c, const double* x, double* y) {
     if (!c || !x || !y) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
+    CacheScope cache_scope(&c->cache);
     hipStream_t st = c->stream;
     const int64_t* perm = c->perm.as<int64_t>();
     HSS_TRY(vec_gather(st, c->mv_x.as<double>(), x, perm, c->n));
@@ -195,6 +208,7 @@ int admm_svm_train_multi(hss_ctx* c, const double* C_list, int32_t nC, double be
     for (int j = 0; j < nC; ++j)
         if (!(C_list[j] > 0.0)) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
+    CacheScope cache_scope(&c->cache);
     int warn = 0;
     if (!c->factored || c->beta != beta) {
         int rc = ulv_factor_impl(c, beta);
@@ -317,6 +331,7 @@ int svm_decision(hss_ctx* c, const double* G, int64_t n_test, const double* z, d
     if (!c || !G || !z || !dec || n_test < 0) return HSS_EINVAL;
     if (!c->compressed) return HSS_ESTATE;
     if (n_test == 0) return HSS_OK;
+    CacheScope cache_scope(&c->cache);
     hipStream_t st = c->stream;
     // dec = K(G, F) (y .* z) + b is the sampling product with the test points as rows, the training points as
     // columns and one "random" column y .* z: the fused Gram + exp + contraction in its 16-column form, of which

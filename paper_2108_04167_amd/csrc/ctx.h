@@ -71,6 +71,8 @@ struct Matvec32 {
 };
 
 struct hss_ctx {
+    BlockCache cache;                       // device blocks between their uses (see common.h); every call on the
+                                            // context opens a CacheScope on it
     hipStream_t stream = nullptr;
     hipStream_t gstream = nullptr;          // the library's own stream for graph capture and replay (default priority)
     hipEvent_t gevent = nullptr;            // orders gstream after / before the caller's stream

@@ -300,6 +300,7 @@ int hss_compress_impl(hss_ctx* c, const double* F, const double* y, int64_t n, i
 
     hipStream_t st = c->stream;
     c->compressed = c->factored = c->basis_cached = false;
+    c->cache.next_epoch();      // the blocks of the previous compression (released just below) stay within reach
     c->lev.clear();
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = s; c->s_pad = s_pad; c->kcap = (int)kcap;
@@ -706,6 +707,7 @@ int hss_import_impl(hss_ctx* c, const double* F, const double* y, int64_t n, int
     }
     hipStream_t st = c->stream;
     c->compressed = c->factored = c->basis_cached = false;
+    c->cache.next_epoch();
     c->lev.clear();
     c->lev.resize(L + 1);
     c->n = n; c->r = r; c->leaf = leaf; c->L = L; c->s = 0; c->s_pad = 0; c->kcap = std::max(kmax, 1);

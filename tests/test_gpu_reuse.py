@@ -128,3 +128,42 @@ def test_destroy_returns_the_device_memory():
     torch.cuda.empty_cache()
     after, _ = torch.cuda.mem_get_info()
     assert before - after < 64 << 20, (before, after)
+
+
+def test_repeated_trains_on_one_context_settle_and_leave_nothing():
+    """The context keeps released device blocks for later allocations of the same size: after the second of several
+    identical trains on one context the device's free memory no longer moves (nothing is allocated or freed on the
+    way), every train gives the bits of the first, a change of shape does not let the footprint grow beyond what
+    the two latest shapes need, and a closed context has returned everything."""
+    import torch
+    Fs, ys, G = _problem(4099, 20, 11)
+    F2, y2, G2 = _problem(1500, 7, 12)
+    warm = binding.Context()
+    _run(warm, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+    warm.close()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    base, _ = torch.cuda.mem_get_info()
+    ctx = binding.Context()
+    first = _run(ctx, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+    free = []
+    for _ in range(4):
+        got = _run(ctx, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+        for key in first:
+            a, b = got[key], first[key]
+            assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, key
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        free.append(torch.cuda.mem_get_info()[0])
+    assert max(free[1:]) - min(free[1:]) <= 4 << 20, free      # (the runtime's own small pools may still move)
+    held_same_shape = base - free[3]
+    # another shape, three times: the blocks of the first shape age out, the footprint follows the new shape
+    for _ in range(3):
+        _run(ctx, F2, y2, G2, 1.0, 64, 128, {}, 1.0, 1.0, 3)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    assert base - torch.cuda.mem_get_info()[0] <= held_same_shape + (64 << 20)
+    ctx.close()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    assert base - torch.cuda.mem_get_info()[0] < 64 << 20
