@@ -219,12 +219,13 @@ __global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __r
             if (tid == 0) a.jtmp[(size_t)node * a.kc + j] = p;
             const double inv = pv > 0.0 ? 1.0 / pv : 0.0;
             const double* Lpp = Lp + (size_t)p * LDP;
-            const double* Gp = Gn + (size_t)p * msz;
+            // G is symmetric and only its lower triangle is kept up to date: entry (p, i) is read at
+            // (max(p, i), min(p, i))
             if (i0 < msz) {
                 double l = 0.0;
                 if (i0 == p) { l = pv; s0 = j + 1; }
                 else if (s0 == 0) {
-                    double c = Gp[i0];
+                    double c = i0 < p ? Gn[(size_t)p * msz + i0] : Gn[(size_t)i0 * msz + p];
                     const double* Li = Lp + (size_t)i0 * LDP;
                     for (int q = 0; q < jj; ++q) c -= Li[q] * Lpp[q];
                     l = c * inv;
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __r
                 double l = 0.0;
                 if (i1 == p) { l = pv; s1 = j + 1; }
                 else if (s1 == 0) {
-                    double c = Gp[i1];
+                    double c = i1 < p ? Gn[(size_t)p * msz + i1] : Gn[(size_t)i1 * msz + p];
                     const double* Li = Lp + (size_t)i1 * LDP;
                     for (int q = 0; q < jj; ++q) c -= Li[q] * Lpp[q];
                     l = c * inv;
@@ -256,11 +257,11 @@ __global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __r
             for (int q = 0; q < nb; ++q) dst[q] = src[q];
         }
         if (stop || p0 + nb >= lim) break;
-        // G -= Lp Lp^T: thread (ty, tx) of a 32 x 16 arrangement owns rows ty + 32 u and columns tx + 16 v of a
-        // 128 x 64 tile
+        // G -= Lp Lp^T on the tiles that hold a part of the lower triangle: thread (ty, tx) of a 32 x 16 arrangement
+        // owns rows ty + 32 u and columns tx + 16 v of a 128 x 64 tile
         const int ty = tid >> 4, tx = tid & 15;
         for (int rb = 0; rb < msz; rb += 128)
-            for (int cb = 0; cb < msz; cb += 64) {
+            for (int cb = 0; cb < msz && cb < rb + 128; cb += 64) {
                 double acc[4][4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(512) void id_chol_kernel(IdLevelArgs a, double* __r
     if (tid == 0) a.rk[node] = rank;
 }
 
-// T = L21 L11^{-1} row by row (one wavefront per row, the row's coefficients spread over the lanes),
+// T = L21 L11^{-1} row by row (a wavefront per group of four rows, a row's coefficients spread over the lanes),
 // and assembly of U (msz x k, row-major at uoff[node]) and of the compact skeleton list J.
 template <int KU>   // kc <= 64 * KU
 __global__ __launch_bounds__(256) void id_finish_kernel(IdLevelArgs a, const int64_t* __restrict__ koff,
@@ -323,20 +324,23 @@ __global__ __launch_bounds__(256) void id_finish_kernel(IdLevelArgs a, const int
     double* Un = U + uoff[node];
     int rend = r0 + a.rows_per_block;
     if (rend > msz) rend = msz;
-    for (int i = r0 + wave; i < rend; i += 4) {
-        const int64_t gi = m0 + i;
-        double* urow = Un + (size_t)i * k;
-        const int s = a.sel[gi];
-        if (s > 0) {
-            for (int c = lane; c < k; c += 64) urow[c] = (c == s - 1) ? 1.0 : 0.0;
-            continue;
-        }
-        double l[KU];
-        const double* lr = a.Lc + (size_t)gi * a.kc;
+    // A wavefront takes every fourth row of the block.  Rows that were chosen as pivots become unit vectors; the
+    // others go through the back substitution RB at a time, so that every row of L11 that is fetched serves RB rows
+    // (the arithmetic of a row is the same whatever its group).
+    constexpr int RB = 4;
+    int grp[RB];
+    int ng = 0;
+    auto substitute = [&]() {
+        if (ng == 0) return;
+        double l[RB][KU];
 #pragma unroll
-        for (int u = 0; u < KU; ++u) {
-            int c = lane + 64 * u;
-            l[u] = c < k ? lr[c] : 0.0;
+        for (int r = 0; r < RB; ++r) {
+            const double* lr = a.Lc + (size_t)(m0 + grp[r < ng ? r : 0]) * a.kc;
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const int c = lane + 64 * u;
+                l[r][u] = (r < ng && c < k) ? lr[c] : 0.0;
+            }
         }
         // back substitution  t L11 = l,  columns from k-1 down to 0; L11[j][c] = Lc[row of pivot j][c], c <= j
 #pragma unroll
@@ -348,24 +352,50 @@ __global__ __launch_bounds__(256) void id_finish_kernel(IdLevelArgs a, const int
                 if (j >= k) continue;
                 const double* Lj = a.Lc + (size_t)(m0 + jt[j]) * a.kc;
                 const double diag = Lj[j];
-                double tj = __shfl(l[u], jj, 64);
-                tj = diag != 0.0 ? tj / diag : 0.0;
-                if (lane == jj) l[u] = tj;
+                double tj[RB];
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    double t = __shfl(l[r][u], jj, 64);
+                    t = diag != 0.0 ? t / diag : 0.0;
+                    if (lane == jj) l[r][u] = t;
+                    tj[r] = t;
+                }
 #pragma unroll
                 for (int w = 0; w < KU; ++w) {
                     if (w <= u) {
-                        int c = lane + 64 * w;
-                        if (c < j) l[w] -= tj * Lj[c];
+                        const int c = lane + 64 * w;
+                        if (c < j) {
+                            const double v = Lj[c];
+#pragma unroll
+                            for (int r = 0; r < RB; ++r) l[r][w] -= tj[r] * v;
+                        }
                     }
                 }
             }
         }
 #pragma unroll
-        for (int u = 0; u < KU; ++u) {
-            int c = lane + 64 * u;
-            if (c < k) urow[c] = l[u];
+        for (int r = 0; r < RB; ++r) {
+            if (r >= ng) continue;
+            double* urow = Un + (size_t)grp[r] * k;
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+                const int c = lane + 64 * u;
+                if (c < k) urow[c] = l[r][u];
+            }
         }
+        ng = 0;
+    };
+    for (int i = r0 + wave; i < rend; i += 4) {
+        const int s = a.sel[m0 + i];
+        if (s > 0) {
+            double* urow = Un + (size_t)i * k;
+            for (int c = lane; c < k; c += 64) urow[c] = (c == s - 1) ? 1.0 : 0.0;
+            continue;
+        }
+        grp[ng++] = i;
+        if (ng == RB) substitute();
     }
+    substitute();
 }
 
 }  // namespace
