@@ -275,6 +275,30 @@ __global__ void bcopy_kernel(const CopyItem* __restrict__ items) {
     }
 }
 
+// Transposing items (dst[r][c] = src[c][r]) through 32 x 32 tiles in LDS, so that both the reads (along r, the
+// contiguous index of src) and the writes (along c) are coalesced; a workgroup walks over the tiles of its item.
+__global__ __launch_bounds__(256) void btrans_kernel(const CopyItem* __restrict__ items) {
+    __shared__ double tile[32][33];
+    const CopyItem it = items[blockIdx.x];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+    const int tr = (it.rows + 31) / 32, tc = (it.cols + 31) / 32;
+    for (int t = blockIdx.y; t < tr * tc; t += gridDim.y) {
+        const int r0 = (t / tc) * 32, c0 = (t % tc) * 32;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + ty + 8 * u, r = r0 + tx;
+            if (c < it.cols && r < it.rows) tile[ty + 8 * u][tx] = it.src[(size_t)c * it.lds + r];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + ty + 8 * u, c = c0 + tx;
+            if (r < it.rows && c < it.cols) it.dst[(size_t)r * it.ldd + c] = tile[tx][ty + 8 * u];
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -293,10 +317,25 @@ int bcopy(hipStream_t st, DescArena& ar, const std::vector<CopyItem>& items) {
     int64_t mx = 0;
     for (auto& it : items) mx = std::max<int64_t>(mx, (int64_t)it.rows * it.cols);
     if (mx == 0) return HSS_OK;
-    const CopyItem* d = (const CopyItem*)ar.push(items.data(), sizeof(CopyItem) * items.size(), st);
-    if (!d) return HSS_ENOMEM;
-    hipLaunchKernelGGL(bcopy_kernel, dim3((unsigned)items.size(), ychunks(mx, 256 * 8)), dim3(256), 0, st, d);
-    HIP_TRY(hipGetLastError());
+    // transposes go through the tiled kernel, everything else through the element-wise one
+    std::vector<CopyItem> tr, pl;
+    for (auto& it : items) (it.mode == COPY_TRANS ? tr : pl).push_back(it);
+    if (!pl.empty()) {
+        const CopyItem* d = (const CopyItem*)ar.push(pl.data(), sizeof(CopyItem) * pl.size(), st);
+        if (!d) return HSS_ENOMEM;
+        hipLaunchKernelGGL(bcopy_kernel, dim3((unsigned)pl.size(), ychunks(mx, 256 * 8)), dim3(256), 0, st, d);
+        HIP_TRY(hipGetLastError());
+    }
+    if (!tr.empty()) {
+        int64_t mt = 0;
+        for (auto& it : tr) mt = std::max<int64_t>(mt, (int64_t)((it.rows + 31) / 32) * ((it.cols + 31) / 32));
+        if (mt > 0) {
+            const CopyItem* d = (const CopyItem*)ar.push(tr.data(), sizeof(CopyItem) * tr.size(), st);
+            if (!d) return HSS_ENOMEM;
+            hipLaunchKernelGGL(btrans_kernel, dim3((unsigned)tr.size(), ychunks(mt, 4)), dim3(256), 0, st, d);
+            HIP_TRY(hipGetLastError());
+        }
+    }
     return HSS_OK;
 }
 
