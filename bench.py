@@ -284,7 +284,9 @@ def main():
                   "bias": out["bias"], "n_margin": out["n_margin"], "test_accuracy_pct": acc, "warnings": st2["warnings"]},
     }
     if not args.neighbours and not args.no_neighbour_leg:
-        # the same train with the paper's own neighbour-based sample in place of K*Omega (one pass, not the metric)
+        # the same train with the paper's own neighbour-based sample in place of K*Omega (one pass, not the metric);
+        # the first context is done: its device memory goes back before the second one is built
+        ctx.close()
         ctx2 = binding.Context()
         ctx2.hss_set_i64("sample_width", w.s)
         ctx2.hss_set_i64("sampling", 1)

@@ -59,10 +59,11 @@ const char* hss_strerror(int code);
 /* Create / destroy a context.  hip_stream: a hipStream_t (0 = the null stream); borrowed.
  * Device memory: a context owns its tree, generators, factors and work space.  Device blocks that a call releases
  * (the work space of a compression or factorization, the state of the previous compression) are kept by the
- * context, up to 32 GiB, and handed to later allocations of about the same size, so that repeated calls with the
- * same problem shape allocate next to nothing; blocks that two compressions in a row did not use are freed, all of
- * them are freed when an allocation fails (it is then tried again) and by hss_destroy, after which nothing the
- * library allocated for the context remains.  One context is used by one thread at a time. */
+ * context, up to 16 GiB, and handed to later allocations of about the same size, so that repeated calls with the
+ * same problem shape allocate next to nothing; blocks that two compressions in a row did not use are freed; when an
+ * allocation fails in any context of the process, the kept blocks of every context are freed before it is tried
+ * again; hss_destroy frees everything, after which nothing the library allocated for the context remains.
+ * One context is used by one thread at a time (different contexts may be used by different threads). */
 int  hss_create(hss_ctx** out, void* hip_stream);
 void hss_destroy(hss_ctx* ctx);
 

@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string.h>
+#include <mutex>
 #include <vector>
 
 #include "../../include/hss_svm.h"
@@ -71,25 +72,68 @@ __device__ __forceinline__ int64_t segment_of(const int64_t* __restrict__ off, i
 // its block hands it to the context's cache, and a reservation takes the smallest cached block that is large
 // enough and at most a quarter larger.  All device work of a context is ordered on its one stream, so a block
 // may change hands without the device-wide wait that hipFree implies.  The cache holds at most `cap` bytes,
-// drops blocks that two compressions in a row did not use, is emptied when an allocation fails (which is then
-// tried again) and when the context is destroyed.
+// drops blocks that two compressions in a row did not use, and is emptied when the context is destroyed.  When an
+// allocation fails anywhere in the process, the caches of ALL contexts are emptied before it is tried again (a
+// cached block is idle by definition, and hipFree waits for whatever its context still has in flight), so what
+// one context keeps can never be the reason another one runs out of memory.
 struct BlockCache {
     struct Blk { void* p; size_t bytes; int epoch; };
+    std::mutex mu;                       // a failed allocation of another context (another thread) may empty this one
     std::vector<Blk> blocks;
     size_t held = 0;
     int epoch = 0;
-    static constexpr size_t cap = size_t(32) << 30;
-    BlockCache() = default;
+    static constexpr size_t cap = size_t(16) << 30;
+    struct Registry {
+        std::mutex mu;
+        std::vector<BlockCache*> all;
+    };
+    static Registry& registry() {
+        static Registry* r = new Registry;      // never destroyed: contexts may outlive the library's static objects
+        return *r;
+    }
+    BlockCache() {
+        Registry& r = registry();
+        std::lock_guard<std::mutex> g(r.mu);
+        r.all.push_back(this);
+    }
     BlockCache(const BlockCache&) = delete;
     BlockCache& operator=(const BlockCache&) = delete;
-    ~BlockCache() { flush(); }
+    ~BlockCache() {
+        {
+            Registry& r = registry();
+            std::lock_guard<std::mutex> g(r.mu);
+            for (size_t i = 0; i < r.all.size(); ++i)
+                if (r.all[i] == this) {
+                    r.all[i] = r.all.back();
+                    r.all.pop_back();
+                    break;
+                }
+        }
+        flush();
+    }
     void flush() {
+        std::lock_guard<std::mutex> g(mu);
         for (const Blk& b : blocks) (void)hipFree(b.p);
         blocks.clear();
         held = 0;
     }
+    // every cache of the process; returns whether anything was freed
+    static bool flush_all() {
+        Registry& r = registry();
+        std::lock_guard<std::mutex> g(r.mu);
+        bool any = false;
+        for (BlockCache* c : r.all) {
+            {
+                std::lock_guard<std::mutex> gc(c->mu);
+                any = any || !c->blocks.empty();
+            }
+            c->flush();
+        }
+        return any;
+    }
     // a new compression starts: blocks that the last two did not take are freed
     void next_epoch() {
+        std::lock_guard<std::mutex> g(mu);
         ++epoch;
         size_t w = 0;
         for (size_t i = 0; i < blocks.size(); ++i) {
@@ -103,12 +147,14 @@ struct BlockCache {
         blocks.resize(w);
     }
     bool give(void* p, size_t bytes) {
+        std::lock_guard<std::mutex> g(mu);
         if (bytes > cap || held + bytes > cap) return false;
         blocks.push_back(Blk{p, bytes, epoch});
         held += bytes;
         return true;
     }
     void* take(size_t nbytes, size_t* got) {
+        std::lock_guard<std::mutex> g(mu);
         const size_t limit = nbytes + nbytes / 4 + (size_t(64) << 10);
         int best = -1;
         for (int i = 0; i < (int)blocks.size(); ++i)
@@ -172,9 +218,8 @@ struct DevBuf {
         if (hipMalloc(&p, nbytes) != hipSuccess) {
             p = nullptr;
             (void)hipGetLastError();
-            // give back what the cache holds and try once more
-            if (!tl_block_cache || tl_block_cache->blocks.empty()) return HSS_ENOMEM;
-            tl_block_cache->flush();
+            // give back what the caches of this process hold and try once more
+            if (!BlockCache::flush_all()) return HSS_ENOMEM;
             if (hipMalloc(&p, nbytes) != hipSuccess) {
                 p = nullptr;
                 (void)hipGetLastError();

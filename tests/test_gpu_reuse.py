@@ -167,3 +167,41 @@ def test_repeated_trains_on_one_context_settle_and_leave_nothing():
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     assert base - torch.cuda.mem_get_info()[0] < 64 << 20
+
+
+def test_failed_allocation_empties_the_caches_of_other_contexts():
+    """What one context keeps for reuse must never be the reason another one runs out of memory: an allocation that
+    fails in context b empties the block cache of the idle context a as well (its blocks go back to the device), and
+    a then still gives the bits it gave before."""
+    import torch
+    Fs, ys, G = _problem(4099, 20, 31)
+    a = binding.Context()
+    first = _run(a, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free1, _ = torch.cuda.mem_get_info()
+    n = 1 << 25
+    F = torch.zeros((n, 1), dtype=torch.float64, device="cuda:0")
+    F[::2] = 1.0
+    y = torch.ones(n, dtype=torch.float64, device="cuda:0")
+    b = binding.Context()
+    b.hss_set_i64("sample_width", 2048)
+    b.hss_set_i64("max_rank", 512)
+    with pytest.raises(binding.HssError) as e:
+        b.hss_compress(F, y, 1.0, 256, 1e-2)
+    code = e.value.code
+    del e                                    # (its traceback holds the call's arguments)
+    assert code == binding.HSS_ENOMEM
+    b.close()
+    del F, y
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free2, _ = torch.cuda.mem_get_info()
+    assert free2 >= free1 + (16 << 20), (free1, free2)          # a's cached work space went back
+    again = _run(a, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+    for key in first:
+        x, z = again[key], first[key]
+        assert np.array_equal(x, z) if isinstance(z, np.ndarray) else x == z, key
+    a.close()
