@@ -273,7 +273,20 @@ int ulv_factor_impl(hss_ctx* c, double beta) {
 
     // temporaries of one chunk of nodes
     DevBuf UT, PT0, PT, G2, L2i, QT, Tmp, Dh, E, Einv, W, Wp, ipiv, cholsc, T1;
-    const int64_t budget = int64_t(48) << 20;   // doubles of m*m per chunk
+    // doubles of m*m per chunk (about a dozen temporaries of that size live at once): larger chunks mean fewer, fuller
+    // launches -- the widest level of the n = 262144 workload goes in one chunk of 512 nodes instead of three of 170,
+    // which matters for the kernels that run one workgroup per node -- so the chunk grows from 48 M to at most 192 M
+    // doubles while the temporaries stay within a quarter of the free device memory
+    int64_t budget = int64_t(48) << 20;
+    {
+        size_t free_b = 0, total_b = 0;
+        if (hipMemGetInfo(&free_b, &total_b) == hipSuccess) {
+            const int64_t fit = (int64_t)((free_b + c->cache.held) / 4 / (12 * sizeof(double)));
+            budget = std::min<int64_t>(int64_t(192) << 20, std::max<int64_t>(budget, fit));
+        } else {
+            (void)hipGetLastError();
+        }
+    }
 
     for (int l = L; l >= 1; --l) {
         Level& lv = c->lev[l];
