@@ -232,23 +232,23 @@ int definiteness_guard(hss_ctx* c) {
     for (int j = 0; j < iters; ++j) {
         HIP_TRY(hipMemcpyAsync(c->mv_x.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
         HSS_TRY(use32 ? hss_matvec_perm32(c) : hss_matvec_perm(c));
+        // alpha = w . v stays on the device for the update; the host sees it together with |w|^2: one wait per step
         HSS_TRY(vec_dot(st, w, vcur.as<double>(), n, part, scal));
-        double a;
-        HIP_TRY(hipMemcpyAsync(&a, scal, sizeof(double), hipMemcpyDeviceToHost, st));
+        HSS_TRY(vec_lanczos_update(st, w, vcur.as<double>(), vprev.as<double>(), scal, bprev, n));
+        HSS_TRY(vec_dot(st, w, w, n, part, scal + 1));
+        double ab[2];
+        HIP_TRY(hipMemcpyAsync(ab, scal, sizeof(ab), hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));
+        const double a = ab[0], b2 = ab[1];
         alpha.push_back(a);
-        HSS_TRY(vec_lanczos_update(st, w, vcur.as<double>(), vprev.as<double>(), a, bprev, n));
-        HSS_TRY(vec_dot(st, w, w, n, part, scal));
-        double b2;
-        HIP_TRY(hipMemcpyAsync(&b2, scal, sizeof(double), hipMemcpyDeviceToHost, st));
-        HIP_TRY(hipStreamSynchronize(st));
         const double b = std::sqrt(b2 > 0.0 ? b2 : 0.0);
         if (!(b > 1e-12 * std::max(1.0, std::fabs(a))) || j + 1 == iters) break;
         ritz.push_back(tridiag_min_eig(alpha, beta));
         if (j >= 11 && std::fabs(ritz[j] - ritz[j - 4]) <= 1e-3 * std::fabs(ritz[j])) break;
         beta.push_back(b);
-        // vprev <- vcur, vcur <- w / b
-        HIP_TRY(hipMemcpyAsync(vprev.p, vcur.p, sizeof(double) * n, hipMemcpyDeviceToDevice, st));
+        // vprev <- vcur (the buffers change roles), vcur <- w / b
+        std::swap(vprev.p, vcur.p);
+        std::swap(vprev.bytes, vcur.bytes);
         HSS_TRY(vec_axpby(st, vcur.as<double>(), w, 1.0 / b, 0.0, n));
         bprev = b;
     }

@@ -20,7 +20,8 @@ int vec_scatter(hipStream_t st, double* dst, const double* src, const int64_t* p
 int vec_mul(hipStream_t st, double* dst, const double* a, const double* b, int64_t n);
 int vec_dot(hipStream_t st, const double* a, const double* b, int64_t n, double* partial_dev, double* out_dev);
 int vec_axpby(hipStream_t st, double* y, const double* x, double a, double b, int64_t n);
-int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, double alpha, double beta, int64_t n);
+int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, const double* alpha_dev, double beta,
+                       int64_t n);
 struct CBox {
     double c[4];        // box bound C of each interleaved column
 };

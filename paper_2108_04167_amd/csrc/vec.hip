@@ -196,9 +196,11 @@ __global__ void axpby_kernel(double* __restrict__ y, const double* __restrict__ 
     if (i < n) y[i] = a * x[i] + b * y[i];
 }
 // w <- w - alpha v - beta vprev
+// (alpha is read from device memory: the dot product that made it has not been seen by the host yet)
 __global__ void lanczos_update_kernel(double* __restrict__ w, const double* __restrict__ v, const double* __restrict__ vp,
-                                      double alpha, double beta, int64_t n) {
+                                      const double* __restrict__ alpha_dev, double beta, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const double alpha = *alpha_dev;
     if (i < n) w[i] = w[i] - alpha * v[i] - beta * vp[i];
 }
 
@@ -305,8 +307,9 @@ int vec_axpby(hipStream_t st, double* y, const double* x, double a, double b, in
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
-int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, double alpha, double beta, int64_t n) {
-    hipLaunchKernelGGL(lanczos_update_kernel, dim3(eb(n)), dim3(256), 0, st, w, v, vp, alpha, beta, n);
+int vec_lanczos_update(hipStream_t st, double* w, const double* v, const double* vp, const double* alpha_dev, double beta,
+                       int64_t n) {
+    hipLaunchKernelGGL(lanczos_update_kernel, dim3(eb(n)), dim3(256), 0, st, w, v, vp, alpha_dev, beta, n);
     HIP_TRY(hipGetLastError());
     return HSS_OK;
 }
