@@ -127,6 +127,10 @@ void hss_destroy(hss_ctx* ctx);
  *                        after / before the context's stream by events; 0 (default): every launch is issued eagerly
  *                        on the context's stream.  The iterates are the same either way; the replay measured 3 - 35 %
  *                        slower per iteration than eager launches on gfx950.
+ *   "block_cache_mib"    how many MiB of released device blocks the context keeps for later allocations of the same
+ *                        size (default 16384; see hss_create).  0: keeps nothing -- every release is a hipFree, every
+ *                        reservation a hipMalloc.  Setting the option frees what is kept at that moment.  Results do
+ *                        not depend on it.
  * Unknown keys and values out of range return HSS_EINVAL. */
 int hss_set_i64(hss_ctx* ctx, const char* key, int64_t v);
 int hss_set_f64(hss_ctx* ctx, const char* key, double v);

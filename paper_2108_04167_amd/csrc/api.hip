@@ -62,6 +62,7 @@ int hss_set_i64(hss_ctx* c, const char* key, int64_t v) {
     else if (!strcmp(key, "cache_basis")) { c->opt_cache_basis = v ? 1 : 0; if (!v) c->basis_cached = false; }
     else if (!strcmp(key, "adaptive_start")) { if (v < 0) return HSS_EINVAL; c->opt_adapt_start = v; }
     else if (!strcmp(key, "adaptive_step")) { if (v < 1) return HSS_EINVAL; c->opt_adapt_step = v; }
+    else if (!strcmp(key, "block_cache_mib")) { if (v < 0 || v > (int64_t(1) << 24)) return HSS_EINVAL; c->cache.set_cap((size_t)v << 20); }
     else return HSS_EINVAL;
     return HSS_OK;
 }

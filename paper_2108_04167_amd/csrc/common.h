@@ -82,7 +82,7 @@ struct BlockCache {
     std::vector<Blk> blocks;
     size_t held = 0;
     int epoch = 0;
-    static constexpr size_t cap = size_t(16) << 30;
+    size_t cap = size_t(16) << 30;       // option "block_cache_mib"; 0 keeps nothing
     struct Registry {
         std::mutex mu;
         std::vector<BlockCache*> all;
@@ -116,6 +116,13 @@ struct BlockCache {
         for (const Blk& b : blocks) (void)hipFree(b.p);
         blocks.clear();
         held = 0;
+    }
+    void set_cap(size_t bytes) {
+        {
+            std::lock_guard<std::mutex> g(mu);
+            cap = bytes;
+        }
+        flush();
     }
     // every cache of the process; returns whether anything was freed
     static bool flush_all() {

@@ -22,6 +22,7 @@ RUNS = [
     "3001 123 128 64 4.0 20 3",                               # leaves of two sizes, features beyond the fused kernels
     "2500 8 128 64 1.5 20 3 sampling=1",
     "1000 300 128 64 6.0 10 2 clustering=1 adaptive_start=128",
+    "4096 8 128 64 1.5 20 3 block_cache_mib=0",              # every release a hipFree, every reservation a hipMalloc
 ]
 
 

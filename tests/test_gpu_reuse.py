@@ -205,3 +205,34 @@ def test_failed_allocation_empties_the_caches_of_other_contexts():
         x, z = again[key], first[key]
         assert np.array_equal(x, z) if isinstance(z, np.ndarray) else x == z, key
     a.close()
+
+
+def test_block_cache_option_changes_no_result():
+    """Option block_cache_mib: 0 keeps nothing (the device's free memory after a train is then what a fresh context
+    leaves), any value gives the same bits; values out of range are refused."""
+    import torch
+    Fs, ys, G = _problem(3001, 20, 41)
+    ref_ctx = binding.Context()
+    ref = _run(ref_ctx, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+    ref = _run(ref_ctx, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)       # second pass: served from the cache
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free_cached, _ = torch.cuda.mem_get_info()
+    ref_ctx.hss_set_i64("block_cache_mib", 0)                           # frees what is kept
+    torch.cuda.synchronize()
+    free_after_off, _ = torch.cuda.mem_get_info()
+    assert free_after_off >= free_cached
+    for mib in (0, 1, 64):
+        ctx = binding.Context()
+        ctx.hss_set_i64("block_cache_mib", mib)
+        for _ in range(2):
+            got = _run(ctx, Fs, ys, G, 2.0, 128, 256, {}, 1.0, 1.0, 3)
+            for key in ref:
+                a, b = got[key], ref[key]
+                assert np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b, (mib, key)
+        ctx.close()
+    for bad in (-1, 1 << 25):
+        with pytest.raises(binding.HssError) as e:
+            ref_ctx.hss_set_i64("block_cache_mib", bad)
+        assert e.value.code == binding.HSS_EINVAL
+    ref_ctx.close()
