@@ -236,3 +236,39 @@ def test_block_cache_option_changes_no_result():
             ref_ctx.hss_set_i64("block_cache_mib", bad)
         assert e.value.code == binding.HSS_EINVAL
     ref_ctx.close()
+
+
+def test_two_contexts_on_two_threads():
+    """Different contexts may be used by different threads at the same time (one context by one thread at a time):
+    two threads, each with a context of its own, train different problems three times over while the other one runs
+    (the library calls release the interpreter lock); every result is the bits of the same train run alone."""
+    import threading
+    probs = [(_problem(3001, 20, 51), 2.0, 128, 256, {}), (_problem(2048, 8, 52), 1.5, 64, 128, {"sampling": 1})]
+    refs = []
+    for (Fs, ys, G), h, leaf, s, opts in probs:
+        c = binding.Context()
+        refs.append(_run(c, Fs, ys, G, h, leaf, s, opts, 1.0, 1.0, 4))
+        c.close()
+    errors = []
+
+    def work(i):
+        try:
+            (Fs, ys, G), h, leaf, s, opts = probs[i]
+            c = binding.Context()
+            for _ in range(3):
+                got = _run(c, Fs, ys, G, h, leaf, s, opts, 1.0, 1.0, 4)
+                for key in refs[i]:
+                    a, b = got[key], refs[i][key]
+                    if not (np.array_equal(a, b) if isinstance(b, np.ndarray) else a == b):
+                        errors.append((i, key))
+            c.close()
+        except Exception as e:          # noqa: BLE001
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads)
+    assert not errors, errors
